@@ -1,0 +1,176 @@
+/*
+ * mhcl.h -- C ABI of libmhcl: the per-token hyper-connection path of mHC-lite
+ * (and of the Sinkhorn-Knopp mHC variant it is compared with) for AMD gfx950.
+ *
+ * One layer of the network updates n residual streams x in R^{n x C} as
+ *
+ *     x_out = H_res x + H_post^T f(H_pre x)                      (Eq. 1)
+ *
+ * where the coefficients are computed per token from the flattened streams
+ * x_hat in R^{1 x nC} (Sec. 3.2, the lines above Eq. 4, Eq. 4 and Eq. 5):
+ *
+ *     x_hat' = RMSNorm(x_hat)
+ *     H_pre  = sigmoid(alpha_pre  x_hat' W_pre  + b_pre)          in R^{1 x n}
+ *     H_post = 2 sigmoid(alpha_post x_hat' W_post + b_post)       in R^{1 x n}
+ *     a      = softmax(alpha_res x_hat' W_res + b_res)            in R^{n!}
+ *     H_res  = sum_k a_k P_k                                      in R^{n x n}
+ *
+ * (P_k: the n! permutation matrices, Theorem 3.1), or, in the Sinkhorn-Knopp
+ * variant (Sec. 2, Eq. 2), H_res = SK(exp(mat(alpha_res x_hat' W_res + b_res)))
+ * with W_res in R^{nC x n^2} and SK repeated sk_iters times.
+ *
+ * f (attention / MLP) is the caller's: the library hands back h = H_pre x, the
+ * caller computes y = f(h) and hands y in.  Backward likewise: the caller
+ * provides the gradient on x_out and on h and receives the gradient on x, y
+ * and the parameters.
+ *
+ * Conventions (they hold for every entry point unless it says otherwise)
+ *  - Every tensor pointer is a DEVICE pointer owned by the caller, dense,
+ *    row-major, 16-byte aligned.  The library never allocates, frees or
+ *    synchronises; every call only enqueues kernels on `stream` (a
+ *    hipStream_t passed as void*; NULL is the default stream).  Scratch memory
+ *    comes from the caller as `ws` / `ws_bytes`, sized by
+ *    mhcl_workspace_bytes(); its contents are undefined before and after a
+ *    call.  There is no global mutable state: calls on different streams with
+ *    disjoint outputs and workspaces may overlap.
+ *  - Stream tensors (x, y, h, x_out and their gradients) have the element
+ *    type desc->io_dtype.  Coefficients, parameters and parameter gradients
+ *    are always fp32.  All arithmetic accumulates in fp32; bf16 results are
+ *    rounded to nearest-even once, from the fp32 value.
+ *  - x is [T, n, C] and is flattened stream-major: x_hat[j*C + c] = x[j][c].
+ *  - W is one [n*C, M] matrix, b is [M]; columns are [res | pre | post] with
+ *    M = n! + 2n (MHCL_RES_LITE; res column k belongs to permutation k) or
+ *    M = n*n + 2n (MHCL_RES_SK; res column i*n + j is entry (i, j)).
+ *    alpha is [3] = {alpha_res, alpha_pre, alpha_post}, in device memory.
+ *  - Permutations are ordered lexicographically as tuples
+ *    (sigma(0), ..., sigma(n-1)); k = 0 is the identity; P_k[i][sigma_k(i)] = 1.
+ *  - RMSNorm has no gain: x_hat' = x_hat / sqrt(mean(x_hat^2) + eps).
+ *  - One SK iteration rescales all columns to sum 1, then all rows.
+ *  - H_res is [T, n, n], H_pre and H_post are [T, n].
+ *  - Every function returns an mhcl_status.  Arguments are validated before
+ *    anything is enqueued, so a non-OK status means nothing ran.  T == 0 is
+ *    valid: per-token tensors may then be null, nothing is read, and the
+ *    sums over tokens (g_W, g_b, g_alpha) are written as zeros.  Errors of the HIP runtime at launch are
+ *    reported as MHCL_ERR_HIP.  Nothing aborts or throws.
+ */
+#ifndef MHCL_H
+#define MHCL_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  MHCL_OK = 0,
+  MHCL_ERR_INVALID_ARG = 1, /* null pointer, misaligned pointer, bad enum, n/C/T out of range */
+  MHCL_ERR_UNSUPPORTED = 2, /* a valid description this build has no kernel for */
+  MHCL_ERR_WORKSPACE = 3,   /* ws is null or smaller than mhcl_workspace_bytes() */
+  MHCL_ERR_HIP = 4          /* a kernel launch was rejected by the runtime */
+} mhcl_status;
+
+enum { MHCL_BF16 = 0, MHCL_F32 = 1 };          /* io_dtype */
+enum { MHCL_RES_LITE = 0, MHCL_RES_SK = 1 };   /* res_mode */
+
+/* operations that need workspace, for mhcl_workspace_bytes() */
+enum {
+  MHCL_OP_COEFFS = 0,
+  MHCL_OP_COEFFS_BWD = 1,
+  MHCL_OP_FWD_COEFFS_PRE = 2,
+  MHCL_OP_BWD_FUSED = 3
+};
+
+typedef struct {
+  int32_t n;        /* residual streams, 1..5                                      */
+  int32_t C;        /* width of one stream; a positive multiple of 8               */
+  int64_t T;        /* tokens, >= 0                                                */
+  int32_t io_dtype; /* MHCL_BF16 | MHCL_F32                                        */
+  int32_t res_mode; /* MHCL_RES_LITE | MHCL_RES_SK                                 */
+  int32_t sk_iters; /* SK repetitions (1..64) for MHCL_RES_SK; ignored for LITE    */
+  float eps;        /* RMSNorm epsilon, >= 0, added to the mean square             */
+} mhcl_desc;
+
+const char *mhcl_status_string(int status);
+
+/* Checks a descriptor (host only; touches no GPU). */
+int mhcl_validate(const mhcl_desc *desc);
+
+/* M: number of logits / columns of W for this descriptor; -1 if invalid. */
+int32_t mhcl_logit_count(const mhcl_desc *desc);
+
+/* Bytes of workspace `op` needs for `desc`; 0 if desc or op is invalid.
+ * Host only. */
+size_t mhcl_workspace_bytes(const mhcl_desc *desc, int op);
+
+/* Host helper: writes the permutation table the library uses (Theorem 3.1;
+ * lexicographic order) into HOST memory sigma[n!][n], sigma[k][i] = column of
+ * the 1 in row i of P_k.  n in 1..5. */
+int mhcl_perm_table(int32_t n, int8_t *sigma);
+
+/* ---- forward ----------------------------------------------------------- */
+
+/* Coefficients of one layer (Sec. 3.2 Eqs. 4-5, or Sec. 2 Eq. 2 in SK mode).
+ * in : x [T,n,C] io, W [nC,M] f32, b [M] f32, alpha [3] f32
+ * out: H_res [T,n,n], H_pre [T,n], H_post [T,n] f32 */
+int mhcl_coeffs(const mhcl_desc *desc, const void *x, const float *W, const float *b,
+                const float *alpha, float *H_res, float *H_pre, float *H_post,
+                void *ws, size_t ws_bytes, void *stream);
+
+/* Pre-aggregate, the argument of f in Eq. 1: h[c] = sum_j H_pre[j] x[j][c].
+ * in : x [T,n,C] io, H_pre [T,n] f32;  out: h [T,C] io */
+int mhcl_pre(const mhcl_desc *desc, const void *x, const float *H_pre, void *h, void *stream);
+
+/* Residual update, Eq. 1 with y = f(h) supplied:
+ * x_out[i][c] = sum_j H_res[i][j] x[j][c] + H_post[i] y[c].
+ * in : x [T,n,C], y [T,C] io; H_res, H_post f32;  out: x_out [T,n,C] io.
+ * x_out must not alias x. */
+int mhcl_post(const mhcl_desc *desc, const void *x, const void *y, const float *H_res,
+              const float *H_post, void *x_out, void *stream);
+
+/* mhcl_coeffs followed by mhcl_pre with fewer passes over x; same results. */
+int mhcl_fwd_coeffs_pre(const mhcl_desc *desc, const void *x, const float *W, const float *b,
+                        const float *alpha, float *H_res, float *H_pre, float *H_post, void *h,
+                        void *ws, size_t ws_bytes, void *stream);
+
+/* ---- backward (chain rule on the definitions above) -------------------- */
+
+/* Backward of mhcl_post, with x, y, H_res, H_post independent inputs.
+ * in : x, y, H_res, H_post as in mhcl_post; g_xout [T,n,C] io
+ * out: g_x [T,n,C] io, OVERWRITTEN with H_res^T g_xout;  g_y [T,C] io;
+ *      g_H_res [T,n,n], g_H_post [T,n] f32 */
+int mhcl_post_bwd(const mhcl_desc *desc, const void *x, const void *y, const float *H_res,
+                  const float *H_post, const void *g_xout, void *g_x, void *g_y,
+                  float *g_H_res, float *g_H_post, void *stream);
+
+/* Backward of mhcl_pre.  g_x is ACCUMULATED into (g_x[j] += H_pre[j] g_h) in
+ * the io type; g_H_pre [T,n] is overwritten. */
+int mhcl_pre_bwd(const mhcl_desc *desc, const void *x, const float *H_pre, const void *g_h,
+                 void *g_x, float *g_H_pre, void *stream);
+
+/* Backward of mhcl_coeffs.  Recomputes the forward from x (nothing is saved
+ * between forward and backward).  g_x is ACCUMULATED into in the io type;
+ * g_W [nC,M], g_b [M], g_alpha [3] (f32) are overwritten with the sums over
+ * all T tokens, added in a fixed order (results are bitwise reproducible). */
+int mhcl_coeffs_bwd(const mhcl_desc *desc, const void *x, const float *W, const float *b,
+                    const float *alpha, const float *g_H_res, const float *g_H_pre,
+                    const float *g_H_post, void *g_x, float *g_W, float *g_b, float *g_alpha,
+                    void *ws, size_t ws_bytes, void *stream);
+
+/* Whole backward of one layer for the loss <g_xout, x_out> + <g_h, h> with y
+ * an independent input: equals mhcl_post_bwd, mhcl_pre_bwd, mhcl_coeffs_bwd
+ * chained, but g_x is summed in fp32 and rounded once, and x is read in fewer
+ * passes.  Coefficients are recomputed from x.
+ * in : x, y, W, b, alpha as in forward; g_xout [T,n,C], g_h [T,C] io
+ * out: g_x [T,n,C], g_y [T,C] io; g_W [nC,M], g_b [M], g_alpha [3] f32; all
+ *      overwritten. */
+int mhcl_bwd_fused(const mhcl_desc *desc, const void *x, const void *y, const float *W,
+                   const float *b, const float *alpha, const void *g_xout, const void *g_h,
+                   void *g_x, void *g_y, float *g_W, float *g_b, float *g_alpha,
+                   void *ws, size_t ws_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MHCL_H */

@@ -1,0 +1,278 @@
+// C ABI of libmhcl: validation, workspace layout, dispatch.  See include/mhcl.h.
+#include "mhcl_common.h"
+#include "mhcl_internal.h"
+
+using namespace mhcl;
+
+namespace {
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int check_desc(const mhcl_desc *d) {
+  if (!d) return MHCL_ERR_INVALID_ARG;
+  if (d->n < 1 || d->n > kMaxN) return MHCL_ERR_INVALID_ARG;
+  if (d->C < 8 || d->C % 8 != 0) return MHCL_ERR_INVALID_ARG;
+  if (d->T < 0) return MHCL_ERR_INVALID_ARG;
+  if (d->io_dtype != MHCL_BF16 && d->io_dtype != MHCL_F32) return MHCL_ERR_INVALID_ARG;
+  if (d->res_mode != MHCL_RES_LITE && d->res_mode != MHCL_RES_SK) return MHCL_ERR_INVALID_ARG;
+  if (d->res_mode == MHCL_RES_SK && (d->sk_iters < 1 || d->sk_iters > kMaxSkIters))
+    return MHCL_ERR_INVALID_ARG;
+  if (!(d->eps >= 0.f)) return MHCL_ERR_INVALID_ARG;
+  // index arithmetic: one launch addresses at most 2^31 - 1 blocks, and a
+  // token's flattened row must fit an int
+  if (static_cast<int64_t>(d->n) * d->C > (1 << 24)) return MHCL_ERR_UNSUPPORTED;
+  if (d->T > (static_cast<int64_t>(1) << 31) - 1) return MHCL_ERR_UNSUPPORTED;
+  if (d->T * (d->C / 4) / 256 > (static_cast<int64_t>(1) << 31) - 1) return MHCL_ERR_UNSUPPORTED;
+  return MHCL_OK;
+}
+
+template <typename... P>
+bool all_ok(P... p) {
+  return ((p != nullptr && aligned16(p)) && ...);
+}
+
+int logits(const mhcl_desc &d) { return res_logits(d.n, d.res_mode) + 2 * d.n; }
+
+// ---- workspace layouts -----------------------------------------------------
+struct CoeffsWs {
+  float *u_raw, *sumsq;
+  size_t bytes;
+  CoeffsWs(const mhcl_desc &d, void *ws) {
+    WsCursor c(ws);
+    const size_t T = static_cast<size_t>(d.T);
+    u_raw = c.take<float>(T * logits(d));
+    sumsq = c.take<float>(T);
+    bytes = c.off;
+  }
+};
+
+struct BwdWs {
+  float *u_raw, *sumsq, *gH_res, *gH_pre, *gH_post, *partials;
+  BwdTokenBufs tok;
+  size_t bytes;
+  BwdWs(const mhcl_desc &d, void *ws, bool need_dots) {
+    WsCursor c(ws);
+    const size_t T = static_cast<size_t>(d.T);
+    const int M = logits(d), n = d.n;
+    u_raw = c.take<float>(T * M);
+    sumsq = c.take<float>(T);
+    tok.H_res = c.take<float>(T * n * n);
+    tok.H_pre = c.take<float>(T * n);
+    tok.H_post = c.take<float>(T * n);
+    tok.vr = c.take<float>(T * M);
+    tok.coefx = c.take<float>(T);
+    tok.gz = c.take<float>(T * (M + 3));
+    gH_res = gH_pre = gH_post = nullptr;
+    if (need_dots) {
+      gH_res = c.take<float>(T * n * n);
+      gH_pre = c.take<float>(T * n);
+      gH_post = c.take<float>(T * n);
+    }
+    const int chunks = gw_chunks_generic(d);
+    partials = chunks > 1 ? c.take<float>(static_cast<size_t>(chunks) * n * d.C * M) : nullptr;
+    bytes = c.off;
+  }
+};
+
+#define MHCL_HIP(expr)                              \
+  do {                                              \
+    if ((expr) != hipSuccess) return MHCL_ERR_HIP;  \
+  } while (0)
+
+}  // namespace
+
+extern "C" {
+
+const char *mhcl_status_string(int status) {
+  switch (status) {
+    case MHCL_OK: return "ok";
+    case MHCL_ERR_INVALID_ARG: return "invalid argument";
+    case MHCL_ERR_UNSUPPORTED: return "unsupported configuration";
+    case MHCL_ERR_WORKSPACE: return "workspace missing or too small";
+    case MHCL_ERR_HIP: return "HIP runtime error at launch";
+  }
+  return "unknown status";
+}
+
+int mhcl_validate(const mhcl_desc *desc) { return check_desc(desc); }
+
+int32_t mhcl_logit_count(const mhcl_desc *desc) {
+  if (check_desc(desc) != MHCL_OK) return -1;
+  return logits(*desc);
+}
+
+size_t mhcl_workspace_bytes(const mhcl_desc *desc, int op) {
+  if (check_desc(desc) != MHCL_OK) return 0;
+  size_t b = 0;
+  switch (op) {
+    case MHCL_OP_COEFFS:
+    case MHCL_OP_FWD_COEFFS_PRE: b = CoeffsWs(*desc, nullptr).bytes; break;
+    case MHCL_OP_COEFFS_BWD: b = BwdWs(*desc, nullptr, false).bytes; break;
+    case MHCL_OP_BWD_FUSED: b = BwdWs(*desc, nullptr, true).bytes; break;
+    default: return 0;
+  }
+  return b < 256 ? 256 : b;
+}
+
+int mhcl_perm_table(int32_t n, int8_t *sigma) {
+  if (!sigma || n < 1 || n > kMaxN) return MHCL_ERR_INVALID_ARG;
+  auto copy = [&](auto nn) {
+    constexpr int N = decltype(nn)::value;
+    for (int k = 0; k < factorial(N); ++k)
+      for (int i = 0; i < N; ++i) sigma[k * N + i] = Perm<N>::tab.s[k][i];
+  };
+  switch (n) {
+    case 1: copy(std::integral_constant<int, 1>{}); break;
+    case 2: copy(std::integral_constant<int, 2>{}); break;
+    case 3: copy(std::integral_constant<int, 3>{}); break;
+    case 4: copy(std::integral_constant<int, 4>{}); break;
+    case 5: copy(std::integral_constant<int, 5>{}); break;
+  }
+  return MHCL_OK;
+}
+
+int mhcl_coeffs(const mhcl_desc *desc, const void *x, const float *W, const float *b,
+                const float *alpha, float *H_res, float *H_pre, float *H_post, void *ws,
+                size_t ws_bytes, void *stream) {
+  if (int e = check_desc(desc)) return e;
+  if (desc->T == 0) return MHCL_OK;   // per-token tensors may then be null
+  if (!all_ok(x, (const void *)W, (const void *)b, (const void *)alpha, (const void *)H_res,
+              (const void *)H_pre, (const void *)H_post))
+    return MHCL_ERR_INVALID_ARG;
+  if (!ws || !aligned16(ws) || ws_bytes < mhcl_workspace_bytes(desc, MHCL_OP_COEFFS))
+    return MHCL_ERR_WORKSPACE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  CoeffsWs w(*desc, ws);
+  MHCL_HIP(launch_proj_generic(*desc, logits(*desc), x, W, w.u_raw, w.sumsq, s));
+  MHCL_HIP(launch_coeffs_epilogue(*desc, w.u_raw, w.sumsq, b, alpha, H_res, H_pre, H_post, s));
+  return MHCL_OK;
+}
+
+int mhcl_pre(const mhcl_desc *desc, const void *x, const float *H_pre, void *h, void *stream) {
+  if (int e = check_desc(desc)) return e;
+  if (desc->T == 0) return MHCL_OK;   // per-token tensors may then be null
+  if (!all_ok(x, (const void *)H_pre, (const void *)h)) return MHCL_ERR_INVALID_ARG;
+  MHCL_HIP(launch_pre(*desc, x, H_pre, h, static_cast<hipStream_t>(stream)));
+  return MHCL_OK;
+}
+
+int mhcl_post(const mhcl_desc *desc, const void *x, const void *y, const float *H_res,
+              const float *H_post, void *x_out, void *stream) {
+  if (int e = check_desc(desc)) return e;
+  if (desc->T == 0) return MHCL_OK;   // per-token tensors may then be null
+  if (!all_ok(x, y, (const void *)H_res, (const void *)H_post, (const void *)x_out))
+    return MHCL_ERR_INVALID_ARG;
+  if (x_out == x) return MHCL_ERR_INVALID_ARG;
+  MHCL_HIP(launch_post(*desc, x, y, H_res, H_post, x_out, static_cast<hipStream_t>(stream)));
+  return MHCL_OK;
+}
+
+int mhcl_fwd_coeffs_pre(const mhcl_desc *desc, const void *x, const float *W, const float *b,
+                        const float *alpha, float *H_res, float *H_pre, float *H_post, void *h,
+                        void *ws, size_t ws_bytes, void *stream) {
+  if (int e = check_desc(desc)) return e;
+  if (desc->T == 0) return MHCL_OK;   // per-token tensors may then be null
+  if (!all_ok(x, (const void *)W, (const void *)b, (const void *)alpha, (const void *)H_res,
+              (const void *)H_pre, (const void *)H_post, (const void *)h))
+    return MHCL_ERR_INVALID_ARG;
+  if (!ws || !aligned16(ws) || ws_bytes < mhcl_workspace_bytes(desc, MHCL_OP_FWD_COEFFS_PRE))
+    return MHCL_ERR_WORKSPACE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  CoeffsWs w(*desc, ws);
+  MHCL_HIP(launch_proj_generic(*desc, logits(*desc), x, W, w.u_raw, w.sumsq, s));
+  MHCL_HIP(launch_coeffs_epilogue(*desc, w.u_raw, w.sumsq, b, alpha, H_res, H_pre, H_post, s));
+  MHCL_HIP(launch_pre(*desc, x, H_pre, h, s));
+  return MHCL_OK;
+}
+
+int mhcl_post_bwd(const mhcl_desc *desc, const void *x, const void *y, const float *H_res,
+                  const float *H_post, const void *g_xout, void *g_x, void *g_y, float *g_H_res,
+                  float *g_H_post, void *stream) {
+  if (int e = check_desc(desc)) return e;
+  if (desc->T == 0) return MHCL_OK;   // per-token tensors may then be null
+  if (!all_ok(x, y, (const void *)H_res, (const void *)H_post, g_xout, (const void *)g_x,
+              (const void *)g_y, (const void *)g_H_res, (const void *)g_H_post))
+    return MHCL_ERR_INVALID_ARG;
+  MHCL_HIP(launch_post_bwd(*desc, x, y, H_res, H_post, g_xout, g_x, g_y, g_H_res, g_H_post,
+                           static_cast<hipStream_t>(stream)));
+  return MHCL_OK;
+}
+
+int mhcl_pre_bwd(const mhcl_desc *desc, const void *x, const float *H_pre, const void *g_h,
+                 void *g_x, float *g_H_pre, void *stream) {
+  if (int e = check_desc(desc)) return e;
+  if (desc->T == 0) return MHCL_OK;   // per-token tensors may then be null
+  if (!all_ok(x, (const void *)H_pre, g_h, (const void *)g_x, (const void *)g_H_pre))
+    return MHCL_ERR_INVALID_ARG;
+  MHCL_HIP(launch_pre_bwd(*desc, x, H_pre, g_h, g_x, g_H_pre, static_cast<hipStream_t>(stream)));
+  return MHCL_OK;
+}
+
+int mhcl_coeffs_bwd(const mhcl_desc *desc, const void *x, const float *W, const float *b,
+                    const float *alpha, const float *g_H_res, const float *g_H_pre,
+                    const float *g_H_post, void *g_x, float *g_W, float *g_b, float *g_alpha,
+                    void *ws, size_t ws_bytes, void *stream) {
+  if (int e = check_desc(desc)) return e;
+  if (desc->T == 0) {   // sums over no tokens; per-token tensors may be null
+    if (!all_ok((const void *)g_W, (const void *)g_b, (const void *)g_alpha))
+      return MHCL_ERR_INVALID_ARG;
+    hipStream_t s0 = static_cast<hipStream_t>(stream);
+    const int M0 = logits(*desc);
+    MHCL_HIP(launch_fill_zero(g_W, static_cast<size_t>(desc->n) * desc->C * M0, s0));
+    MHCL_HIP(launch_fill_zero(g_b, M0, s0));
+    MHCL_HIP(launch_fill_zero(g_alpha, 3, s0));
+    return MHCL_OK;
+  }
+  if (!all_ok(x, (const void *)W, (const void *)b, (const void *)alpha, (const void *)g_H_res,
+              (const void *)g_H_pre, (const void *)g_H_post, (const void *)g_x, (const void *)g_W,
+              (const void *)g_b, (const void *)g_alpha))
+    return MHCL_ERR_INVALID_ARG;
+  if (!ws || !aligned16(ws) || ws_bytes < mhcl_workspace_bytes(desc, MHCL_OP_COEFFS_BWD))
+    return MHCL_ERR_WORKSPACE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int M = logits(*desc);
+  BwdWs w(*desc, ws, false);
+  MHCL_HIP(launch_proj_generic(*desc, M, x, W, w.u_raw, w.sumsq, s));
+  MHCL_HIP(launch_coeffs_bwd_epilogue(*desc, w.u_raw, w.sumsq, b, alpha, g_H_res, g_H_pre,
+                                      g_H_post, w.tok, s));
+  MHCL_HIP(launch_gx_generic(*desc, M, false, x, W, nullptr, nullptr, w.tok, g_x, nullptr, s));
+  MHCL_HIP(launch_gw_generic(*desc, M, x, w.tok.vr, w.partials, g_W, s));
+  MHCL_HIP(launch_param_sums(*desc, M, w.tok.gz, g_b, g_alpha, s));
+  return MHCL_OK;
+}
+
+int mhcl_bwd_fused(const mhcl_desc *desc, const void *x, const void *y, const float *W,
+                   const float *b, const float *alpha, const void *g_xout, const void *g_h,
+                   void *g_x, void *g_y, float *g_W, float *g_b, float *g_alpha, void *ws,
+                   size_t ws_bytes, void *stream) {
+  if (int e = check_desc(desc)) return e;
+  if (desc->T == 0) {   // sums over no tokens; per-token tensors may be null
+    if (!all_ok((const void *)g_W, (const void *)g_b, (const void *)g_alpha))
+      return MHCL_ERR_INVALID_ARG;
+    hipStream_t s0 = static_cast<hipStream_t>(stream);
+    const int M0 = logits(*desc);
+    MHCL_HIP(launch_fill_zero(g_W, static_cast<size_t>(desc->n) * desc->C * M0, s0));
+    MHCL_HIP(launch_fill_zero(g_b, M0, s0));
+    MHCL_HIP(launch_fill_zero(g_alpha, 3, s0));
+    return MHCL_OK;
+  }
+  if (!all_ok(x, y, (const void *)W, (const void *)b, (const void *)alpha, g_xout, g_h,
+              (const void *)g_x, (const void *)g_y, (const void *)g_W, (const void *)g_b,
+              (const void *)g_alpha))
+    return MHCL_ERR_INVALID_ARG;
+  if (!ws || !aligned16(ws) || ws_bytes < mhcl_workspace_bytes(desc, MHCL_OP_BWD_FUSED))
+    return MHCL_ERR_WORKSPACE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int M = logits(*desc);
+  BwdWs w(*desc, ws, true);
+  MHCL_HIP(launch_proj_generic(*desc, M, x, W, w.u_raw, w.sumsq, s));
+  MHCL_HIP(launch_bwd_dots(*desc, x, y, g_xout, g_h, w.gH_res, w.gH_post, w.gH_pre, s));
+  MHCL_HIP(launch_coeffs_bwd_epilogue(*desc, w.u_raw, w.sumsq, b, alpha, w.gH_res, w.gH_pre,
+                                      w.gH_post, w.tok, s));
+  MHCL_HIP(launch_gx_generic(*desc, M, true, x, W, g_xout, g_h, w.tok, g_x, g_y, s));
+  MHCL_HIP(launch_gw_generic(*desc, M, x, w.tok.vr, w.partials, g_W, s));
+  MHCL_HIP(launch_param_sums(*desc, M, w.tok.gz, g_b, g_alpha, s));
+  return MHCL_OK;
+}
+
+}  // extern "C"

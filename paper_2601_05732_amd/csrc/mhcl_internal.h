@@ -1,0 +1,76 @@
+// Host-side declarations shared by the translation units of libmhcl.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/mhcl.h"
+
+namespace mhcl {
+
+inline int host_factorial(int n) { return n <= 1 ? 1 : n * host_factorial(n - 1); }
+inline int res_logits(int n, int mode) { return mode == MHCL_RES_LITE ? host_factorial(n) : n * n; }
+inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
+
+// Carves a caller-provided workspace into 256-byte aligned pieces.
+struct WsCursor {
+  char *base;
+  size_t off = 0;
+  explicit WsCursor(void *p) : base(static_cast<char *>(p)) {}
+  template <typename T>
+  T *take(size_t count) {
+    T *p = base ? reinterpret_cast<T *>(base + off) : nullptr;
+    off += align_up(count * sizeof(T));
+    return p;
+  }
+};
+
+// Per-token results of the backward's coefficient stage, all [T, ...] fp32.
+struct BwdTokenBufs {
+  float *H_res;   // [T, n*n]
+  float *H_pre;   // [T, n]
+  float *H_post;  // [T, n]
+  float *vr;      // [T, M]   r * alpha_g * g_z   (the vector multiplied with W and x)
+  float *coefx;   // [T]      (r^2 / nC) <vr, u_raw>
+  float *gz;      // [T, M+3] g_z, then the three per-group sums of g_z * u
+};
+
+// ---- generic (plain ALU) kernels: any n in 1..5, bf16 or f32 streams -----
+hipError_t launch_proj_generic(const mhcl_desc &d, int M, const void *x, const float *W,
+                               float *u_raw, float *sumsq, hipStream_t s);
+hipError_t launch_coeffs_epilogue(const mhcl_desc &d, const float *u_raw, const float *sumsq,
+                                  const float *b, const float *alpha, float *H_res, float *H_pre,
+                                  float *H_post, hipStream_t s);
+hipError_t launch_pre(const mhcl_desc &d, const void *x, const float *H_pre, void *h, hipStream_t s);
+hipError_t launch_post(const mhcl_desc &d, const void *x, const void *y, const float *H_res,
+                       const float *H_post, void *x_out, hipStream_t s);
+hipError_t launch_post_bwd(const mhcl_desc &d, const void *x, const void *y, const float *H_res,
+                           const float *H_post, const void *g_xout, void *g_x, void *g_y,
+                           float *g_H_res, float *g_H_post, hipStream_t s);
+hipError_t launch_pre_bwd(const mhcl_desc &d, const void *x, const float *H_pre, const void *g_h,
+                          void *g_x, float *g_H_pre, hipStream_t s);
+// dots only: g_H_res = <g_xout[i], x[j]>, g_H_post = <g_xout[i], y>, g_H_pre = <g_h, x[j]>
+hipError_t launch_bwd_dots(const mhcl_desc &d, const void *x, const void *y, const void *g_xout,
+                           const void *g_h, float *g_H_res, float *g_H_post, float *g_H_pre,
+                           hipStream_t s);
+hipError_t launch_coeffs_bwd_epilogue(const mhcl_desc &d, const float *u_raw, const float *sumsq,
+                                      const float *b, const float *alpha, const float *g_H_res,
+                                      const float *g_H_pre, const float *g_H_post,
+                                      const BwdTokenBufs &o, hipStream_t s);
+// fused == true : g_x = H_res^T g_xout + H_pre g_h + W vr - x coefx ; g_y = H_post g_xout
+// fused == false: g_x += W vr - x coefx
+hipError_t launch_gx_generic(const mhcl_desc &d, int M, bool fused, const void *x, const float *W,
+                             const void *g_xout, const void *g_h, const BwdTokenBufs &o, void *g_x,
+                             void *g_y, hipStream_t s);
+int gw_chunks_generic(const mhcl_desc &d);
+hipError_t launch_gw_generic(const mhcl_desc &d, int M, const void *x, const float *vr,
+                             float *partials, float *g_W, hipStream_t s);
+// a fill kernel (safe under graph capture, unlike a memset node)
+hipError_t launch_fill_zero(float *p, size_t count, hipStream_t s);
+// dst[c] = sum_t src[t*ld + c], c < cols, fixed order
+hipError_t launch_colsum(const float *src, int64_t T, int ld, int cols, float *dst, hipStream_t s);
+// g_b [M] and g_alpha [3] from gz [T, M+3]
+hipError_t launch_param_sums(const mhcl_desc &d, int M, const float *gz, float *g_b, float *g_alpha,
+                             hipStream_t s);
+
+}  // namespace mhcl

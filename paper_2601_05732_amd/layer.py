@@ -1,0 +1,69 @@
+"""Buffers of one hyper-connection layer on the GPU and the library calls that
+fill them: a convenience over :mod:`paper_2601_05732_amd.binding` used by the
+tests, the smoke check and the benchmark.  It computes nothing itself.
+"""
+from __future__ import annotations
+
+import torch
+
+from . import binding as mhcl
+
+
+def desc_for(wl, T=None) -> mhcl.Desc:
+    """Descriptor for a workload record (fields n, C, T, io, res_mode, sk_iters, eps)."""
+    return mhcl.Desc(wl.n, wl.C, wl.T if T is None else T,
+                     mhcl.BF16 if wl.io == "bf16" else mhcl.F32,
+                     mhcl.RES_LITE if wl.res_mode == "lite" else mhcl.RES_SK,
+                     wl.sk_iters, wl.eps)
+
+
+class GpuLayer:
+    """Buffers of one layer on the GPU plus the calls that fill them."""
+
+    def __init__(self, d: mhcl.Desc, inp: dict):
+        self.d, self.inp = d, inp
+        dev, f, io = inp["x"].device, torch.float32, d.torch_dtype
+        T, n, C, M = d.T, d.n, d.C, d.M
+        e = lambda *s, dt=f: torch.empty(s, device=dev, dtype=dt)
+        self.H_res, self.H_pre, self.H_post = e(T, n, n), e(T, n), e(T, n)
+        self.h, self.x_out = e(T, C, dt=io), e(T, n, C, dt=io)
+        self.g_x, self.g_y = e(T, n, C, dt=io), e(T, C, dt=io)
+        self.g_W, self.g_b, self.g_alpha = e(n * C, M), e(M), e(3)
+        self.g_H_res, self.g_H_pre, self.g_H_post = e(T, n, n), e(T, n), e(T, n)
+        nb = max(mhcl.workspace_bytes(d, op) for op in
+                 (mhcl.OP_COEFFS, mhcl.OP_COEFFS_BWD, mhcl.OP_FWD_COEFFS_PRE, mhcl.OP_BWD_FUSED))
+        self.ws = torch.empty(nb, device=dev, dtype=torch.uint8)
+
+    # forward, separable calls
+    def forward_separable(self):
+        i, d = self.inp, self.d
+        mhcl.mhcl_coeffs(d, i["x"], i["W"], i["b"], i["alpha"], self.H_res, self.H_pre,
+                         self.H_post, self.ws)
+        mhcl.mhcl_pre(d, i["x"], self.H_pre, self.h)
+        mhcl.mhcl_post(d, i["x"], i["y"], self.H_res, self.H_post, self.x_out)
+
+    # forward, fused calls (what the benchmark times)
+    def forward_fused(self):
+        i, d = self.inp, self.d
+        mhcl.mhcl_fwd_coeffs_pre(d, i["x"], i["W"], i["b"], i["alpha"], self.H_res, self.H_pre,
+                                 self.H_post, self.h, self.ws)
+        mhcl.mhcl_post(d, i["x"], i["y"], self.H_res, self.H_post, self.x_out)
+
+    def backward_separable(self):
+        i, d = self.inp, self.d
+        mhcl.mhcl_post_bwd(d, i["x"], i["y"], self.H_res, self.H_post, i["g_xout"], self.g_x,
+                           self.g_y, self.g_H_res, self.g_H_post)
+        mhcl.mhcl_pre_bwd(d, i["x"], self.H_pre, i["g_h"], self.g_x, self.g_H_pre)
+        mhcl.mhcl_coeffs_bwd(d, i["x"], i["W"], i["b"], i["alpha"], self.g_H_res, self.g_H_pre,
+                             self.g_H_post, self.g_x, self.g_W, self.g_b, self.g_alpha, self.ws)
+
+    def backward_fused(self):
+        i, d = self.inp, self.d
+        mhcl.mhcl_bwd_fused(d, i["x"], i["y"], i["W"], i["b"], i["alpha"], i["g_xout"], i["g_h"],
+                            self.g_x, self.g_y, self.g_W, self.g_b, self.g_alpha, self.ws)
+
+    def step(self):
+        """One pass of the whole hot path: forward (two calls around the
+        caller's f) and the fused backward."""
+        self.forward_fused()
+        self.backward_fused()

@@ -1,0 +1,82 @@
+"""Host-side checks of the C ABI: the library loads, exports every symbol the
+header declares, validates arguments before touching a GPU, and its
+permutation table equals the library enumeration.  No GPU needed."""
+import ctypes
+import itertools
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2601_05732_amd as mhcl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "mhcl.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(mhcl_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    declared = _declared_symbols()
+    assert len(declared) >= 13
+    L = mhcl.lib()
+    for name in declared:
+        assert hasattr(L, name), name
+    assert all(mhcl.exported_symbols().values())
+
+
+@pytest.mark.parametrize("n", [1, 2, 3, 4, 5])
+def test_perm_table_matches_library_enumeration(n):
+    got = mhcl.perm_table(n)
+    assert got.tolist() == [list(p) for p in itertools.permutations(range(n))]
+
+
+def test_logit_count_and_workspace():
+    d = mhcl.Desc(4, 4096, 32768, mhcl.BF16, mhcl.RES_LITE)
+    assert mhcl.logit_count(d) == 32
+    assert mhcl.logit_count(mhcl.Desc(5, 2560, 16, mhcl.BF16)) == 130
+    assert mhcl.logit_count(mhcl.Desc(4, 4096, 16, mhcl.BF16, mhcl.RES_SK)) == 24
+    for op in (mhcl.OP_COEFFS, mhcl.OP_COEFFS_BWD, mhcl.OP_FWD_COEFFS_PRE, mhcl.OP_BWD_FUSED):
+        assert mhcl.workspace_bytes(d, op) >= 256
+        assert mhcl.workspace_bytes(mhcl.Desc(4, 64, 0, mhcl.F32), op) >= 256
+    assert mhcl.workspace_bytes(d, 99) == 0
+
+
+@pytest.mark.parametrize("kw", [
+    dict(n=0), dict(n=6), dict(C=0), dict(C=12), dict(T=-1), dict(io_dtype=7), dict(res_mode=3),
+    dict(res_mode=mhcl.RES_SK, sk_iters=0), dict(res_mode=mhcl.RES_SK, sk_iters=1000),
+    dict(eps=-1.0), dict(eps=float("nan")),
+])
+def test_invalid_descriptors_are_rejected(kw):
+    base = dict(n=4, C=64, T=16, io_dtype=mhcl.BF16, res_mode=mhcl.RES_LITE, sk_iters=20, eps=1e-6)
+    base.update(kw)
+    d = mhcl.Desc(**base)
+    assert mhcl.lib().mhcl_validate(ctypes.byref(d.c)) == 1
+    assert mhcl.logit_count(d) == -1
+    assert mhcl.workspace_bytes(d, mhcl.OP_COEFFS) == 0
+
+
+def test_null_and_misaligned_pointers_fail_before_any_launch():
+    L = mhcl.lib()
+    d = mhcl.Desc(4, 64, 16, mhcl.F32)
+    ok = 4096  # an aligned, never dereferenced address: validation fails first
+    assert L.mhcl_pre(ctypes.byref(d.c), None, ok, ok, None) == 1
+    assert L.mhcl_pre(ctypes.byref(d.c), ok, ok + 4, ok, None) == 1
+    assert L.mhcl_post(ctypes.byref(d.c), ok, ok, ok, ok, ok, None) == 1     # x_out aliases x
+    assert L.mhcl_coeffs(ctypes.byref(d.c), ok, ok, ok, ok, ok, ok, ok, None, 0, None) == 3
+    assert L.mhcl_coeffs(ctypes.byref(d.c), ok, ok, ok, ok, ok, ok, ok, ok, 16, None) == 3
+    assert L.mhcl_bwd_fused(ctypes.byref(d.c), *([ok] * 12), None, 0, None) == 3
+    assert L.mhcl_coeffs(None, ok, ok, ok, ok, ok, ok, ok, ok, 1 << 20, None) == 1
+    assert mhcl.lib().mhcl_status_string(3).decode().startswith("workspace")
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    d = mhcl.Desc(2, 8, 4, mhcl.F32)
+    x = torch.zeros(4, 2, 8)
+    with pytest.raises(ValueError):
+        mhcl.mhcl_pre(d, x, torch.zeros(4, 2), torch.zeros(4, 8))

@@ -1,0 +1,180 @@
+"""GPU parity: libmhcl (through its C ABI) against the fp64 oracle on the same
+seeded input bits.
+
+Tolerances (metric: max_e |got - ref| / max(|ref_e|, rms(ref)) per tensor):
+  * f32 streams: 1e-5 on every output;
+  * bf16 streams: 2e-2 on bf16 outputs; fp32 coefficients 1e-4 (fp32
+    accumulation over nC terms); parameter gradients 2e-3 (their inputs, the
+    C-long dot products feeding g_z, are fp32 sums of bf16 products);
+  * H_res rows and columns sum to 1 within 1e-6 (permutation form).
+"""
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as si
+from gpu_harness import GpuLayer, desc_for, oracle_reference, rel_err, to_np64
+
+pytestmark = pytest.mark.gpu
+
+TOL_F32 = 1e-5
+TOL_BF16_OUT = 2e-2
+TOL_BF16_COEF = 1e-4
+TOL_BF16_PARAM = 2e-3
+
+
+def _tols(wl):
+    if wl.io == "f32":
+        return TOL_F32, TOL_F32, TOL_F32
+    return TOL_BF16_OUT, TOL_BF16_COEF, TOL_BF16_PARAM
+
+
+def _check_forward(L, ref, wl, tokens=None):
+    t_out, t_coef, _ = _tols(wl)
+    sel = (lambda a: a) if tokens is None else (lambda a: a[tokens])
+    for name, tol in [("H_res", t_coef), ("H_pre", t_coef), ("H_post", t_coef),
+                      ("h", t_out), ("x_out", t_out)]:
+        got = sel(to_np64(getattr(L, name)))
+        e = rel_err(got, ref[name])
+        assert e <= tol, f"{name}: {e:.3e} > {tol}"
+    if wl.res_mode == "lite":
+        H = to_np64(L.H_res)
+        assert np.abs(H.sum(axis=1) - 1).max() <= 1e-6 and np.abs(H.sum(axis=2) - 1).max() <= 1e-6
+        assert H.min() >= 0.0
+
+
+def _check_backward(L, ref, wl, tokens=None, params=True):
+    t_out, _, t_par = _tols(wl)
+    sel = (lambda a: a) if tokens is None else (lambda a: a[tokens])
+    for name in ("g_x", "g_y"):
+        e = rel_err(sel(to_np64(getattr(L, name))), ref[name])
+        assert e <= t_out, f"{name}: {e:.3e} > {t_out}"
+    if params:
+        for name in ("g_W", "g_b", "g_alpha"):
+            e = rel_err(to_np64(getattr(L, name)), ref[name])
+            assert e <= t_par, f"{name}: {e:.3e} > {t_par}"
+
+
+def _small(name, **kw):
+    base = dict(name=name, n=4, C=64, T=256, io="bf16")
+    base.update(kw)
+    return si.Workload(**base)
+
+
+SMALL_CASES = [
+    si.WORKLOADS["tiny_f32"],                                  # the stated all-fp32 case
+    _small("f32_sk", io="f32", res_mode="sk"),
+    _small("bf16_n4", C=256, T=333),                           # ragged T
+    _small("bf16_n4_sk", C=256, T=129, res_mode="sk"),
+    _small("bf16_n1", n=1, C=128, T=67),
+    _small("bf16_n2", n=2, C=64, T=130),
+    _small("bf16_n3", n=3, C=1024, T=77),
+    _small("bf16_n5", n=5, C=96, T=45),
+    _small("bf16_n5_sk", n=5, C=64, T=33, res_mode="sk"),
+    _small("f32_n3", n=3, C=40, T=19, io="f32"),
+    _small("bf16_c4096", C=4096, T=70),                        # full width, several tiles + tail
+    _small("one_token", C=64, T=1),
+    _small("sk_3iters", C=64, T=40, res_mode="sk", sk_iters=3),
+]
+
+
+@pytest.mark.parametrize("wl", SMALL_CASES, ids=lambda w: w.name)
+def test_forward_and_backward_match_oracle(wl):
+    print(f"case {wl}", flush=True)
+    inp = si.make_inputs(wl, seed=0, device="cuda")
+    ref = oracle_reference(inp, wl)
+    L = GpuLayer(desc_for(wl), inp)
+    L.forward_separable()
+    torch.cuda.synchronize()
+    _check_forward(L, ref, wl)
+    sep = {k: getattr(L, k).clone() for k in ("H_res", "H_pre", "H_post", "h", "x_out")}
+    L.forward_fused()
+    torch.cuda.synchronize()
+    _check_forward(L, ref, wl)
+    for k, v in sep.items():      # fused and separable forward agree
+        assert rel_err(to_np64(getattr(L, k)), to_np64(v)) <= (1e-6 if k.startswith("H") else _tols(wl)[0])
+    L.backward_fused()
+    torch.cuda.synchronize()
+    _check_backward(L, ref, wl)
+    fused_gx = to_np64(L.g_x)
+    L.backward_separable()
+    torch.cuda.synchronize()
+    # the separable chain rounds g_x to the stream type three times
+    t_out = _tols(wl)[0]
+    assert rel_err(to_np64(L.g_x), ref["g_x"]) <= (t_out if wl.io == "f32" else 2 * t_out)
+    assert rel_err(to_np64(L.g_x), fused_gx) <= (t_out if wl.io == "f32" else 2 * t_out)
+    _check_backward(L, ref, wl) if wl.io == "f32" else None
+    for name, tol in [("g_H_res", _tols(wl)[2]), ("g_H_pre", _tols(wl)[2]), ("g_H_post", _tols(wl)[2])]:
+        assert rel_err(to_np64(getattr(L, name)), ref[name]) <= tol, name
+
+
+def test_paper_initialisation_case():
+    # W = 0, alpha = 0.01, init biases (Sec. 4 "Initialization"): coefficients are
+    # input independent and the block is almost an ordinary residual connection
+    wl = _small("init", C=128, T=50, alpha=(0.01, 0.01, 0.01))
+    inp = si.make_inputs(wl, seed=1, device="cuda")
+    W, b, al = si.paper_init_params(wl.n, wl.C, "lite", one_index=1)
+    inp["W"], inp["b"], inp["alpha"] = (torch.tensor(a, device="cuda") for a in (W, b, al))
+    ref = oracle_reference(inp, wl)
+    L = GpuLayer(desc_for(wl), inp)
+    L.step()
+    torch.cuda.synchronize()
+    _check_forward(L, ref, wl)
+    _check_backward(L, ref, wl, params=False)
+    H = to_np64(L.H_res)
+    assert abs(H[0, 0, 0] - 0.9940079055) < 1e-6 and abs(H[0, 0, 1] - 0.0019973648) < 1e-7
+    # g_W is not identically zero here even though W is (alpha g_z x_hat'^T)
+    for name in ("g_W", "g_b", "g_alpha"):
+        assert rel_err(to_np64(getattr(L, name)), ref[name]) <= TOL_BF16_PARAM, name
+
+
+def test_empty_input_is_a_no_op():
+    wl = _small("empty", T=0)
+    inp = si.make_inputs(wl, seed=0, device="cuda")
+    L = GpuLayer(desc_for(wl), inp)
+    L.g_W.fill_(7.0); L.g_b.fill_(7.0); L.g_alpha.fill_(7.0)
+    L.forward_separable(); L.forward_fused(); L.backward_fused()
+    torch.cuda.synchronize()
+    assert float(L.g_W.abs().max()) == 0.0 and float(L.g_b.abs().max()) == 0.0
+    assert float(L.g_alpha.abs().max()) == 0.0
+    L.g_W.fill_(7.0)
+    L.backward_separable()
+    torch.cuda.synchronize()
+    assert float(L.g_W.abs().max()) == 0.0
+
+
+def test_zero_input_with_eps():
+    # all-zero streams: x_hat' = 0, logits equal the bias
+    wl = _small("zeros", C=64, T=9)
+    inp = si.make_inputs(wl, seed=0, device="cuda")
+    inp["x"].zero_()
+    ref = oracle_reference(inp, wl)
+    L = GpuLayer(desc_for(wl), inp)
+    L.step()
+    torch.cuda.synchronize()
+    _check_forward(L, ref, wl)
+    _check_backward(L, ref, wl)
+
+
+def test_results_are_bitwise_reproducible():
+    wl = _small("repro", C=512, T=300)
+    inp = si.make_inputs(wl, seed=3, device="cuda")
+    L = GpuLayer(desc_for(wl), inp)
+    L.step(); torch.cuda.synchronize()
+    first = {k: getattr(L, k).clone() for k in ("H_res", "h", "x_out", "g_x", "g_y", "g_W", "g_b", "g_alpha")}
+    for _ in range(3):
+        L.step(); torch.cuda.synchronize()
+        for k, v in first.items():
+            assert torch.equal(getattr(L, k), v), k
+
+
+def test_stream_sum_conservation_full_width():
+    # column sums of H_res are 1  =>  sum_i x_out[i] = sum_j x[j] + (sum_i H_post[i]) y
+    wl = _small("conserve", C=4096, T=512)
+    inp = si.make_inputs(wl, seed=4, device="cuda")
+    L = GpuLayer(desc_for(wl), inp)
+    L.forward_fused(); torch.cuda.synchronize()
+    lhs = L.x_out.double().sum(dim=1)
+    rhs = inp["x"].double().sum(dim=1) + L.H_post.double().sum(dim=1, keepdim=True) * inp["y"].double()
+    # each of the n outputs is rounded to bf16 once: |err| <= n * 2^-9 * max|x_out|
+    assert float((lhs - rhs).abs().max()) <= 4 * 2.0 ** -9 * float(L.x_out.abs().max())
