@@ -1,0 +1,210 @@
+#!/usr/bin/env python3
+"""Benchmark of the mHC-lite hyper-connection hot path on one MI355X.
+
+A step is one pass of the whole path over one batch of synthetic input, all
+tensors resident in HBM: mhcl_fwd_coeffs_pre, mhcl_post (the two forward calls
+around the caller's layer function) and mhcl_bwd_fused.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+                    [--no-cpu-baseline] [--detail]
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBS = 8000.0   # MI355X published HBM3E peak
+
+STAGES = {1: "fwd_proj", 2: "fwd_pre", 3: "post", 4: "bwd_reduce", 5: "bwd_out", 6: "bwd_gw"}
+
+
+def stage_bytes(stage: int, n: int, C: int, T: int, e: int) -> int:
+    """Algorithmic HBM bytes of one launch of a stage: every stream tensor the
+    stage consumes or produces crosses HBM once (U = C*e bytes per token row);
+    per-token coefficients and W (MiBs) are ignored."""
+    U = C * e
+    per_token = {
+        1: n * U,                # read x
+        2: (n + 1) * U,          # read x, write h
+        3: (2 * n + 1) * U,      # read x, y; write x_out
+        4: (2 * n + 2) * U,      # read x, g_xout, y, g_h
+        5: (3 * n + 2) * U,      # read x, g_xout, g_h; write g_x, g_y
+        6: n * U,                # read x (g_W itself is MiBs)
+    }[stage]
+    return per_token * T
+
+
+def _hip_runtime():
+    """The HIP runtime this process already has loaded (torch's)."""
+    path = None
+    with open("/proc/self/maps") as f:
+        for line in f:
+            if "libamdhip64" in line:
+                path = line.split()[-1]
+                break
+    return ctypes.CDLL(path or "libamdhip64.so")
+
+
+class HipEvents:
+    def __init__(self, count):
+        self.rt = _hip_runtime()
+        self.rt.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self.rt.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p,
+                                                ctypes.c_void_p]
+        self.rt.hipEventDestroy.argtypes = [ctypes.c_void_p]
+        self.ev = []
+        for _ in range(count):
+            h = ctypes.c_void_p()
+            if self.rt.hipEventCreate(ctypes.byref(h)) != 0:
+                raise RuntimeError("hipEventCreate failed")
+            self.ev.append(h)
+
+    def elapsed_ms(self, i, j):
+        ms = ctypes.c_float()
+        rc = self.rt.hipEventElapsedTime(ctypes.byref(ms), self.ev[i], self.ev[j])
+        if rc != 0:
+            raise RuntimeError(f"hipEventElapsedTime failed ({rc})")
+        return ms.value
+
+    def close(self):
+        for h in self.ev:
+            self.rt.hipEventDestroy(h)
+
+
+def cpu_baseline(inp, wl, sample_tokens):
+    """The fp64 oracle, as it stands, on the first `sample_tokens` tokens of the
+    same workload (forward + backward), timed on the host cores."""
+    import numpy as np
+    import torch
+
+    import oracle
+    f64 = lambda t: t[:sample_tokens].detach().to("cpu", torch.float64).numpy()
+    full = lambda t: t.detach().to("cpu", torch.float64).numpy()
+    x, y, gxo, gh = f64(inp["x"]), f64(inp["y"]), f64(inp["g_xout"]), f64(inp["g_h"])
+    W, b, al = full(inp["W"]), full(inp["b"]), full(inp["alpha"])
+    oracle.backward(x[:8], W, b, al, y[:8], gxo[:8], gh[:8], eps=wl.eps, res_mode=wl.res_mode,
+                    iters=wl.sk_iters)   # loads the library, warms the caches
+    t0 = time.perf_counter()
+    oracle.backward(x, W, b, al, y, gxo, gh, eps=wl.eps, res_mode=wl.res_mode, iters=wl.sk_iters)
+    dt = time.perf_counter() - t0
+    cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    return {"value": sample_tokens / dt, "unit": "tokens/s", "cores": cores, "kind": "oracle",
+            "sample": f"first {sample_tokens} of {wl.T} tokens, forward+backward, fp64, "
+                      f"{dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="n4_c4096")
+    ap.add_argument("--cpu-sample", type=int, default=16384)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--detail", action="store_true", help="per-stage times on stderr")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (tokens are independent, so the path "
+              "shards over tokens; no multi-GPU figure is produced). Use --gpus 1.",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import paper_2601_05732_amd as mhcl
+    import synth_inputs as si
+
+    wl = si.WORKLOADS[args.workload]
+    torch.cuda.set_device(0)
+    inp = si.make_inputs(wl, seed=0, device="cuda:0")
+    if not wl.backward:
+        raise SystemExit("bench.py times forward+backward; pick a workload with backward")
+    d = mhcl.desc_for(wl)
+    L = mhcl.GpuLayer(d, inp)
+    e = 2 if wl.io == "bf16" else 4
+    lib = mhcl.lib()
+    lib.mhcl_profile_next_call.argtypes = [ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
+
+    def step(stage=0, ev=None, i0=0):
+        """One pass; optionally bracket `stage` with events ev[i0], ev[i0+1]."""
+        arm = lambda on: lib.mhcl_profile_next_call(stage if on else 0, ev.ev[i0] if on else None,
+                                                    ev.ev[i0 + 1] if on else None)
+        i, dd = L.inp, L.d
+        arm(stage in (1, 2))
+        mhcl.mhcl_fwd_coeffs_pre(dd, i["x"], i["W"], i["b"], i["alpha"], L.H_res, L.H_pre,
+                                 L.H_post, L.h, L.ws)
+        arm(stage == 3)
+        mhcl.mhcl_post(dd, i["x"], i["y"], L.H_res, L.H_post, L.x_out)
+        arm(stage in (4, 5, 6))
+        mhcl.mhcl_bwd_fused(dd, i["x"], i["y"], i["W"], i["b"], i["alpha"], i["g_xout"], i["g_h"],
+                            L.g_x, L.g_y, L.g_W, L.g_b, L.g_alpha, L.ws)
+
+    # warmup; the last warmup passes also find the stage that takes longest
+    probe = HipEvents(2)
+    for _ in range(max(0, args.warmup - len(STAGES))):
+        step()
+    stage_ms = {}
+    for st in STAGES:
+        step(st, probe, 0)
+        torch.cuda.synchronize()
+        stage_ms[st] = probe.elapsed_ms(0, 1)
+    probe.close()
+    dominant = max(stage_ms, key=stage_ms.get)
+    if args.detail:
+        for st, ms in stage_ms.items():
+            gbs = stage_bytes(st, wl.n, wl.C, wl.T, e) / ms / 1e6
+            print(f"[stage] {STAGES[st]:>10}: {ms:8.3f} ms  {gbs:8.1f} GB/s algorithmic",
+                  file=sys.stderr)
+
+    ev = HipEvents(2 * args.steps)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step(dominant, ev, 2 * k)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    kern_ms = sum(ev.elapsed_ms(2 * k, 2 * k + 1) for k in range(args.steps)) / args.steps
+    ev.close()
+
+    ms_per_step = dt / args.steps * 1e3
+    tokens_per_s = wl.T / (dt / args.steps)
+    floor_bytes = ((3 * wl.n + 2) + (3 * wl.n + 3)) * wl.C * e * wl.T
+    achieved = stage_bytes(dominant, wl.n, wl.C, wl.T, e) / kern_ms / 1e6
+    out = {
+        "metric": "tokens/s + achieved HBM GB/s, fused mHC-lite fwd+bwd, n=4 C=4096 32k tok"
+                  if args.workload == "n4_c4096" else f"tokens/s, fused fwd+bwd, {args.workload}",
+        "value": tokens_per_s,
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16" if wl.io == "bf16" else "f32",
+        "data": "synthetic",
+        "config": {"workload": f"{args.workload}: n={wl.n} C={wl.C} T={wl.T} "
+                               f"{wl.io} streams, fp32 accumulate, {wl.res_mode} H_res, "
+                               "forward (coeffs+pre, post) + fused backward",
+                   "path_hbm_gbs_algorithmic": floor_bytes / (dt / args.steps) / 1e9,
+                   "path_frac_of_peak": floor_bytes / (dt / args.steps) / 1e9 / PEAK_HBM_GBS},
+        "roofline": {"bound": "hbm", "kernel": STAGES[dominant], "achieved": achieved,
+                     "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": achieved / PEAK_HBM_GBS,
+                     "kernel_ms": kern_ms, "traffic": None},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(inp, wl, min(args.cpu_sample, wl.T))
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

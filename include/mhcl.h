@@ -170,6 +170,30 @@ int mhcl_bwd_fused(const mhcl_desc *desc, const void *x, const void *y, const fl
                    void *g_x, void *g_y, float *g_W, float *g_b, float *g_alpha,
                    void *ws, size_t ws_bytes, void *stream);
 
+/* ---- measurement aids (no part of the method) --------------------------- */
+
+/* Kernel stages that can be bracketed with events. */
+enum {
+  MHCL_STAGE_NONE = 0,
+  MHCL_STAGE_FWD_PROJ = 1,   /* projection + coefficients kernel of the forward          */
+  MHCL_STAGE_FWD_PRE = 2,    /* h = H_pre x                                              */
+  MHCL_STAGE_POST = 3,       /* x_out = H_res x + H_post y                               */
+  MHCL_STAGE_BWD_REDUCE = 4, /* backward pass 1: all per-token reductions + coefficients */
+  MHCL_STAGE_BWD_OUT = 5,    /* backward pass 2: g_x and g_y                             */
+  MHCL_STAGE_BWD_GW = 6      /* backward: g_W, the reduction over tokens                 */
+};
+
+/* Arms the NEXT library call made by this host thread: it records the
+ * hipEvent_t `ev_start` on its stream right before the first kernel of `stage`
+ * and `ev_stop` right after the last one, then disarms.  Both events are the
+ * caller's (created with timing enabled).  State is per host thread. */
+int mhcl_profile_next_call(int stage, void *ev_start, void *ev_stop);
+
+/* Plain device-to-device copy kernel of `bytes` bytes (a multiple of 16; both
+ * pointers 16-byte aligned): the yardstick for achievable HBM bandwidth and
+ * for calibrating hardware byte counters. */
+int mhcl_debug_copy(void *dst, const void *src, size_t bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

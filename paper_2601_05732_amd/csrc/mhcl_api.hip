@@ -36,18 +36,21 @@ int logits(const mhcl_desc &d) { return res_logits(d.n, d.res_mode) + 2 * d.n; }
 // ---- workspace layouts -----------------------------------------------------
 struct CoeffsWs {
   float *u_raw, *sumsq;
+  char *Wp;   // packed W (fast path only)
   size_t bytes;
   CoeffsWs(const mhcl_desc &d, void *ws) {
     WsCursor c(ws);
     const size_t T = static_cast<size_t>(d.T);
     u_raw = c.take<float>(T * logits(d));
     sumsq = c.take<float>(T);
+    Wp = fast_path_ok(d) ? c.take<char>(packed_w_b_bytes(d, logits(d))) : nullptr;
     bytes = c.off;
   }
 };
 
 struct BwdWs {
   float *u_raw, *sumsq, *gH_res, *gH_pre, *gH_post, *partials;
+  char *Wp;
   BwdTokenBufs tok;
   size_t bytes;
   BwdWs(const mhcl_desc &d, void *ws, bool need_dots) {
@@ -70,14 +73,47 @@ struct BwdWs {
     }
     const int chunks = gw_chunks_generic(d);
     partials = chunks > 1 ? c.take<float>(static_cast<size_t>(chunks) * n * d.C * M) : nullptr;
+    Wp = fast_path_ok(d) ? c.take<char>(packed_w_b_bytes(d, M)) : nullptr;
     bytes = c.off;
   }
+};
+
+// Per-thread arming of event brackets around one stage (mhcl_profile_next_call).
+thread_local int t_stage = MHCL_STAGE_NONE;
+thread_local hipEvent_t t_ev_start = nullptr, t_ev_stop = nullptr;
+
+struct StageBracket {
+  bool on;
+  hipStream_t s;
+  StageBracket(int stage, hipStream_t stream) : on(stage == t_stage && t_ev_start), s(stream) {
+    if (on) (void)hipEventRecord(t_ev_start, s);
+  }
+  ~StageBracket() {
+    if (on) (void)hipEventRecord(t_ev_stop, s);
+  }
+};
+struct Disarm {
+  ~Disarm() { t_stage = MHCL_STAGE_NONE; }
 };
 
 #define MHCL_HIP(expr)                              \
   do {                                              \
     if ((expr) != hipSuccess) return MHCL_ERR_HIP;  \
   } while (0)
+
+// u_raw, sumsq of every token: MFMA kernel when the shape allows, else plain ALU
+hipError_t run_projection(const mhcl_desc &d, const void *x, const float *W, float *u_raw,
+                          float *sumsq, char *Wp, int stage, hipStream_t s) {
+  const int M = logits(d);
+  if (fast_path_ok(d)) {
+    hipError_t e = launch_pack_w_b(d, M, W, Wp, s);
+    if (e != hipSuccess) return e;
+    StageBracket br(stage, s);
+    return launch_proj_mfma(d, M, x, Wp, u_raw, sumsq, s);
+  }
+  StageBracket br(stage, s);
+  return launch_proj_generic(d, M, x, W, u_raw, sumsq, s);
+}
 
 }  // namespace
 
@@ -108,7 +144,9 @@ size_t mhcl_workspace_bytes(const mhcl_desc *desc, int op) {
     case MHCL_OP_COEFFS:
     case MHCL_OP_FWD_COEFFS_PRE: b = CoeffsWs(*desc, nullptr).bytes; break;
     case MHCL_OP_COEFFS_BWD: b = BwdWs(*desc, nullptr, false).bytes; break;
-    case MHCL_OP_BWD_FUSED: b = BwdWs(*desc, nullptr, true).bytes; break;
+    case MHCL_OP_BWD_FUSED:
+      b = fast_bwd_ok(*desc) ? FastBwdWs(*desc, nullptr).bytes : BwdWs(*desc, nullptr, true).bytes;
+      break;
     default: return 0;
   }
   return b < 256 ? 256 : b;
@@ -131,6 +169,22 @@ int mhcl_perm_table(int32_t n, int8_t *sigma) {
   return MHCL_OK;
 }
 
+int mhcl_profile_next_call(int stage, void *ev_start, void *ev_stop) {
+  if (stage < MHCL_STAGE_NONE || stage > MHCL_STAGE_BWD_GW) return MHCL_ERR_INVALID_ARG;
+  if (stage != MHCL_STAGE_NONE && (!ev_start || !ev_stop)) return MHCL_ERR_INVALID_ARG;
+  t_stage = stage;
+  t_ev_start = static_cast<hipEvent_t>(ev_start);
+  t_ev_stop = static_cast<hipEvent_t>(ev_stop);
+  return MHCL_OK;
+}
+
+int mhcl_debug_copy(void *dst, const void *src, size_t bytes, void *stream) {
+  if (!dst || !src || !aligned16(dst) || !aligned16(src) || bytes % 16 != 0)
+    return MHCL_ERR_INVALID_ARG;
+  MHCL_HIP(launch_copy(dst, src, bytes, static_cast<hipStream_t>(stream)));
+  return MHCL_OK;
+}
+
 int mhcl_coeffs(const mhcl_desc *desc, const void *x, const float *W, const float *b,
                 const float *alpha, float *H_res, float *H_pre, float *H_post, void *ws,
                 size_t ws_bytes, void *stream) {
@@ -143,7 +197,8 @@ int mhcl_coeffs(const mhcl_desc *desc, const void *x, const float *W, const floa
     return MHCL_ERR_WORKSPACE;
   hipStream_t s = static_cast<hipStream_t>(stream);
   CoeffsWs w(*desc, ws);
-  MHCL_HIP(launch_proj_generic(*desc, logits(*desc), x, W, w.u_raw, w.sumsq, s));
+  Disarm disarm;
+  MHCL_HIP(run_projection(*desc, x, W, w.u_raw, w.sumsq, w.Wp, MHCL_STAGE_FWD_PROJ, s));
   MHCL_HIP(launch_coeffs_epilogue(*desc, w.u_raw, w.sumsq, b, alpha, H_res, H_pre, H_post, s));
   return MHCL_OK;
 }
@@ -152,6 +207,8 @@ int mhcl_pre(const mhcl_desc *desc, const void *x, const float *H_pre, void *h, 
   if (int e = check_desc(desc)) return e;
   if (desc->T == 0) return MHCL_OK;   // per-token tensors may then be null
   if (!all_ok(x, (const void *)H_pre, (const void *)h)) return MHCL_ERR_INVALID_ARG;
+  Disarm disarm;
+  StageBracket br(MHCL_STAGE_FWD_PRE, static_cast<hipStream_t>(stream));
   MHCL_HIP(launch_pre(*desc, x, H_pre, h, static_cast<hipStream_t>(stream)));
   return MHCL_OK;
 }
@@ -163,6 +220,8 @@ int mhcl_post(const mhcl_desc *desc, const void *x, const void *y, const float *
   if (!all_ok(x, y, (const void *)H_res, (const void *)H_post, (const void *)x_out))
     return MHCL_ERR_INVALID_ARG;
   if (x_out == x) return MHCL_ERR_INVALID_ARG;
+  Disarm disarm;
+  StageBracket br(MHCL_STAGE_POST, static_cast<hipStream_t>(stream));
   MHCL_HIP(launch_post(*desc, x, y, H_res, H_post, x_out, static_cast<hipStream_t>(stream)));
   return MHCL_OK;
 }
@@ -179,9 +238,13 @@ int mhcl_fwd_coeffs_pre(const mhcl_desc *desc, const void *x, const float *W, co
     return MHCL_ERR_WORKSPACE;
   hipStream_t s = static_cast<hipStream_t>(stream);
   CoeffsWs w(*desc, ws);
-  MHCL_HIP(launch_proj_generic(*desc, logits(*desc), x, W, w.u_raw, w.sumsq, s));
+  Disarm disarm;
+  MHCL_HIP(run_projection(*desc, x, W, w.u_raw, w.sumsq, w.Wp, MHCL_STAGE_FWD_PROJ, s));
   MHCL_HIP(launch_coeffs_epilogue(*desc, w.u_raw, w.sumsq, b, alpha, H_res, H_pre, H_post, s));
-  MHCL_HIP(launch_pre(*desc, x, H_pre, h, s));
+  {
+    StageBracket br(MHCL_STAGE_FWD_PRE, s);
+    MHCL_HIP(launch_pre(*desc, x, H_pre, h, s));
+  }
   return MHCL_OK;
 }
 
@@ -232,7 +295,8 @@ int mhcl_coeffs_bwd(const mhcl_desc *desc, const void *x, const float *W, const 
   hipStream_t s = static_cast<hipStream_t>(stream);
   const int M = logits(*desc);
   BwdWs w(*desc, ws, false);
-  MHCL_HIP(launch_proj_generic(*desc, M, x, W, w.u_raw, w.sumsq, s));
+  Disarm disarm;
+  MHCL_HIP(run_projection(*desc, x, W, w.u_raw, w.sumsq, w.Wp, MHCL_STAGE_BWD_REDUCE, s));
   MHCL_HIP(launch_coeffs_bwd_epilogue(*desc, w.u_raw, w.sumsq, b, alpha, g_H_res, g_H_pre,
                                       g_H_post, w.tok, s));
   MHCL_HIP(launch_gx_generic(*desc, M, false, x, W, nullptr, nullptr, w.tok, g_x, nullptr, s));
@@ -264,12 +328,36 @@ int mhcl_bwd_fused(const mhcl_desc *desc, const void *x, const void *y, const fl
     return MHCL_ERR_WORKSPACE;
   hipStream_t s = static_cast<hipStream_t>(stream);
   const int M = logits(*desc);
+  Disarm disarm;
+  if (fast_bwd_ok(*desc)) {
+    FastBwdWs f(*desc, ws);
+    MHCL_HIP(launch_pack_w_b(*desc, M, W, f.Wp, s));
+    MHCL_HIP(launch_pack_w_a(*desc, M, W, f.Wa, s));
+    {
+      StageBracket br(MHCL_STAGE_BWD_REDUCE, s);
+      MHCL_HIP(launch_bwd_reduce(*desc, M, x, y, g_xout, g_h, f, s));
+    }
+    MHCL_HIP(launch_bwd_epilogue_fast(*desc, b, alpha, f, s));
+    {
+      StageBracket br(MHCL_STAGE_BWD_OUT, s);
+      MHCL_HIP(launch_bwd_out(*desc, x, g_xout, g_h, f, g_x, g_y, s));
+    }
+    {
+      StageBracket br(MHCL_STAGE_BWD_GW, s);
+      MHCL_HIP(launch_bwd_gw(*desc, M, x, f, g_W, s));
+    }
+    MHCL_HIP(launch_param_sums(*desc, M, f.gz, g_b, g_alpha, s));
+    return MHCL_OK;
+  }
   BwdWs w(*desc, ws, true);
-  MHCL_HIP(launch_proj_generic(*desc, M, x, W, w.u_raw, w.sumsq, s));
+  MHCL_HIP(run_projection(*desc, x, W, w.u_raw, w.sumsq, w.Wp, MHCL_STAGE_BWD_REDUCE, s));
   MHCL_HIP(launch_bwd_dots(*desc, x, y, g_xout, g_h, w.gH_res, w.gH_post, w.gH_pre, s));
   MHCL_HIP(launch_coeffs_bwd_epilogue(*desc, w.u_raw, w.sumsq, b, alpha, w.gH_res, w.gH_pre,
                                       w.gH_post, w.tok, s));
-  MHCL_HIP(launch_gx_generic(*desc, M, true, x, W, g_xout, g_h, w.tok, g_x, g_y, s));
+  {
+    StageBracket br(MHCL_STAGE_BWD_OUT, s);
+    MHCL_HIP(launch_gx_generic(*desc, M, true, x, W, g_xout, g_h, w.tok, g_x, g_y, s));
+  }
   MHCL_HIP(launch_gw_generic(*desc, M, x, w.tok.vr, w.partials, g_W, s));
   MHCL_HIP(launch_param_sums(*desc, M, w.tok.gz, g_b, g_alpha, s));
   return MHCL_OK;

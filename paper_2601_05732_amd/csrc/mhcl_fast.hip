@@ -1,0 +1,833 @@
+// bf16 fast path of libmhcl for gfx950: the thin projections run on the MFMA
+// units (v_mfma_f32_16x16x32_bf16, fp32 accumulate), everything else streams.
+//
+// x is exactly bf16; W is fp32 and is split into two bf16 parts (hi + lo), so
+// x_hat W carries ~16 mantissa bits of W at twice the MFMA work, which stays a
+// small fraction of the time the HBM stream needs.
+#include "mhcl_common.h"
+#include "mhcl_internal.h"
+#include "mhcl_mfma.h"
+
+namespace mhcl {
+
+namespace {
+
+__device__ __forceinline__ void split_bf16(float w, uint16_t &hi, uint16_t &lo) {
+  hi = f32_to_bf16(w);
+  lo = f32_to_bf16(w - bf16_to_f32(hi));
+}
+
+// W [K, M] fp32 -> B layout (see mhcl_mfma.h).  One thread per (block pair, lane).
+__global__ __launch_bounds__(256) void pack_w_b_kernel(const float *__restrict__ W, int K, int M,
+                                                       int NT, uint4 *__restrict__ Wp) {
+  const int idx = blockIdx.x * 256 + threadIdx.x;
+  const int lane = idx & 63, blk = idx >> 6;   // blk = s*NT + j
+  if (blk >= (K / 32) * NT) return;
+  const int s = blk / NT, j = blk % NT, r = lane & 15, q = lane >> 4;
+  const int col = 16 * j + r;
+  uint16_t hi[8], lo[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const int k = 32 * s + 8 * q + e;
+    const float w = col < M ? W[static_cast<size_t>(k) * M + col] : 0.f;
+    split_bf16(w, hi[e], lo[e]);
+  }
+  uint4 vh, vl;
+  vh.x = hi[0] | (uint32_t(hi[1]) << 16); vh.y = hi[2] | (uint32_t(hi[3]) << 16);
+  vh.z = hi[4] | (uint32_t(hi[5]) << 16); vh.w = hi[6] | (uint32_t(hi[7]) << 16);
+  vl.x = lo[0] | (uint32_t(lo[1]) << 16); vl.y = lo[2] | (uint32_t(lo[3]) << 16);
+  vl.z = lo[4] | (uint32_t(lo[5]) << 16); vl.w = lo[6] | (uint32_t(lo[7]) << 16);
+  Wp[(static_cast<size_t>(blk) * 2 + 0) * 64 + lane] = vh;
+  Wp[(static_cast<size_t>(blk) * 2 + 1) * 64 + lane] = vl;
+}
+
+// ---------------------------------------------------------------------------
+// Forward projection: u_raw[t][m] = sum_k x_hat[t][k] W[k][m], sumsq[t] = sum_k
+// x_hat[t][k]^2 (RMSNorm's statistic), both from ONE read of x.
+//
+// Block = 4 waves, each wave owns 32 tokens (two 16-token A tiles) and walks
+// the whole K = nC range; the block's waves share each chunk of packed W
+// through LDS (double buffered).  A tiles come straight from HBM in MFMA lane
+// order: lane (r, q) reads 16 bytes of token r at column 32 s + 8 q.
+// sum(x^2) is the diagonal of the tile's Gram matrix A A^T, one more MFMA with
+// the A tile as both operands.
+template <int NT>
+struct ProjCfg {
+  static constexpr int KC = NT <= 2 ? 8 : (NT == 3 ? 4 : 2);   // K steps per chunk
+  static constexpr int kChunkVec = KC * NT * 2 * 64;           // uint4 per chunk
+  static constexpr int kLdsBytes = 2 * kChunkVec * 16;
+};
+
+template <int NT>
+__global__ __launch_bounds__(256, 2) void proj_mfma_kernel(const uint16_t *__restrict__ x,
+                                                           const uint4 *__restrict__ Wp, int K,
+                                                           int M, int64_t T,
+                                                           float *__restrict__ u_raw,
+                                                           float *__restrict__ sumsq) {
+  using Cfg = ProjCfg<NT>;
+  constexpr int KC = Cfg::KC, TG = 2;
+  extern __shared__ uint4 lds[];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int r = lane & 15, q = lane >> 4;
+  const int64_t tw = static_cast<int64_t>(blockIdx.x) * 128 + wave * 32;
+  const uint16_t *row[TG];
+#pragma unroll
+  for (int g = 0; g < TG; ++g) {
+    int64_t t = tw + g * 16 + r;
+    if (t > T - 1) t = T - 1;
+    row[g] = x + t * K + q * 8;
+  }
+  const int nsteps = K / 32;
+  const int nchunks = (nsteps + KC - 1) / KC;
+
+  f32x4 acc[TG][NT], ss[TG];
+#pragma unroll
+  for (int g = 0; g < TG; ++g) {
+    ss[g] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int j = 0; j < NT; ++j) acc[g][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+
+  constexpr int WV = Cfg::kChunkVec / 256;   // uint4 of W each thread stages per chunk
+  uint4 a[2][TG][KC], wst[WV];
+
+  auto load_a = [&](uint4 (&dst)[TG][KC], int c) {
+#pragma unroll
+    for (int s = 0; s < KC; ++s) {
+      const int step = c * KC + s;
+      if (step < nsteps) {
+#pragma unroll
+        for (int g = 0; g < TG; ++g)
+          dst[g][s] = *reinterpret_cast<const uint4 *>(row[g] + step * 32);
+      }
+    }
+  };
+  auto load_w = [&](int c) {
+    const size_t base = static_cast<size_t>(c) * Cfg::kChunkVec;
+    const size_t lim = static_cast<size_t>(nsteps) * NT * 2 * 64;
+#pragma unroll
+    for (int i = 0; i < WV; ++i) {
+      const size_t e = base + i * 256 + threadIdx.x;
+      wst[i] = e < lim ? Wp[e] : uint4{0, 0, 0, 0};
+    }
+  };
+  auto store_w = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < WV; ++i) lds[buf * Cfg::kChunkVec + i * 256 + threadIdx.x] = wst[i];
+  };
+  auto compute = [&](const uint4 (&av)[TG][KC], int buf, int c) {
+    const uint4 *wb = lds + buf * Cfg::kChunkVec;
+#pragma unroll
+    for (int s = 0; s < KC; ++s) {
+      if (c * KC + s < nsteps) {
+#pragma unroll
+        for (int j = 0; j < NT; ++j) {
+          const uint4 bh = wb[((s * NT + j) * 2 + 0) * 64 + lane];
+          const uint4 bl = wb[((s * NT + j) * 2 + 1) * 64 + lane];
+#pragma unroll
+          for (int g = 0; g < TG; ++g) {
+            acc[g][j] = mfma16(av[g][s], bh, acc[g][j]);
+            acc[g][j] = mfma16(av[g][s], bl, acc[g][j]);
+          }
+        }
+#pragma unroll
+        for (int g = 0; g < TG; ++g) ss[g] = mfma16(av[g][s], av[g][s], ss[g]);
+      }
+    }
+  };
+
+  load_a(a[0], 0);
+  load_w(0);
+  store_w(0);
+  __syncthreads();
+  for (int c = 0; c < nchunks; c += 2) {
+    if (c + 1 < nchunks) { load_a(a[1], c + 1); load_w(c + 1); }
+    compute(a[0], 0, c);
+    if (c + 1 < nchunks) store_w(1);
+    __syncthreads();
+    if (c + 1 < nchunks) {
+      if (c + 2 < nchunks) { load_a(a[0], c + 2); load_w(c + 2); }
+      compute(a[1], 1, c + 1);
+      if (c + 2 < nchunks) store_w(0);
+      __syncthreads();
+    }
+  }
+
+  // D layout: lane (r, q) holds logit 16 j + r for tokens 4 q + i
+#pragma unroll
+  for (int g = 0; g < TG; ++g) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int64_t t = tw + g * 16 + 4 * q + i;
+      if (t < T) {
+#pragma unroll
+        for (int j = 0; j < NT; ++j) {
+          const int col = 16 * j + r;
+          if (col < M) u_raw[t * M + col] = acc[g][j][i];
+        }
+      }
+    }
+    // Gram diagonal: token r sits at row r = 4 q + i  <=>  q == r / 4, i == r % 4
+    if ((r >> 2) == q) {
+      const int i = r & 3;
+      const float v = i == 0 ? ss[g][0] : (i == 1 ? ss[g][1] : (i == 2 ? ss[g][2] : ss[g][3]));
+      const int64_t t = tw + g * 16 + r;
+      if (t < T) sumsq[t] = v;
+    }
+  }
+}
+
+
+// W [K, M] fp32 -> A layout (see mhcl_mfma.h).  One thread per (block pair, lane).
+__global__ __launch_bounds__(256) void pack_w_a_kernel(const float *__restrict__ W, int K, int M,
+                                                       int MS, uint4 *__restrict__ Wa) {
+  const int idx = blockIdx.x * 256 + threadIdx.x;
+  const int lane = idx & 63, blk = idx >> 6;   // blk = (s*2 + h)*MS + ms
+  if (blk >= (K / 32) * 2 * MS) return;
+  const int ms = blk % MS, h = (blk / MS) & 1, s = blk / (2 * MS);
+  const int r = lane & 15, q = lane >> 4;
+  const int k = 32 * s + 8 * (r >> 2) + 4 * h + (r & 3);
+  uint16_t hi[8], lo[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const int col = 32 * ms + 8 * q + e;
+    const float w = col < M ? W[static_cast<size_t>(k) * M + col] : 0.f;
+    split_bf16(w, hi[e], lo[e]);
+  }
+  uint4 vh, vl;
+  vh.x = hi[0] | (uint32_t(hi[1]) << 16); vh.y = hi[2] | (uint32_t(hi[3]) << 16);
+  vh.z = hi[4] | (uint32_t(hi[5]) << 16); vh.w = hi[6] | (uint32_t(hi[7]) << 16);
+  vl.x = lo[0] | (uint32_t(lo[1]) << 16); vl.y = lo[2] | (uint32_t(lo[3]) << 16);
+  vl.z = lo[4] | (uint32_t(lo[5]) << 16); vl.w = lo[6] | (uint32_t(lo[7]) << 16);
+  Wa[(static_cast<size_t>(blk) * 2 + 0) * 64 + lane] = vh;
+  Wa[(static_cast<size_t>(blk) * 2 + 1) * 64 + lane] = vl;
+}
+
+// sum over 8 bf16 pairs-of-products: acc + <a, b>, products exact, fp32 sums
+__device__ __forceinline__ float dot8_bf16(const uint4 &a, const uint4 &b, float acc) {
+  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a.x), __builtin_bit_cast(bf16x2, b.x), acc, false);
+  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a.y), __builtin_bit_cast(bf16x2, b.y), acc, false);
+  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a.z), __builtin_bit_cast(bf16x2, b.z), acc, false);
+  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a.w), __builtin_bit_cast(bf16x2, b.w), acc, false);
+  return acc;
+}
+
+// ---------------------------------------------------------------------------
+// Backward pass 1: every per-token reduction of the backward from ONE read of
+// x, g_xout, y, g_h:
+//   u_raw, sumsq                      (recomputed projection, as in forward)
+//   g_H_res[i][j] = <g_xout[i], x[j]>, g_H_post[i] = <g_xout[i], y>,
+//   g_H_pre[j]    = <g_h, x[j]>       (reductions over C)
+// Block = 4 waves x 16 tokens.  The loop runs over 32-column steps of C; at
+// each step a lane holds, for its token, 8 columns of all n streams of x and
+// g_xout and of y and g_h, feeds the x tiles to the MFMA projection (W blocks
+// of that step staged in LDS, double buffered) and the dot products to
+// v_dot2_f32_bf16.  The four lanes that share a token are summed at the end.
+template <int N, int NT>
+struct ReduceCfg {
+  static constexpr int kStageVec = N * NT * 2 * 64;            // uint4 of W per column step
+  static constexpr int WV = (kStageVec + 255) / 256;
+  static constexpr int kLdsBytes = 2 * kStageVec * 16;
+};
+
+template <int N, int NT>
+__global__ __launch_bounds__(256, 2) void bwd_reduce_kernel(
+    const uint16_t *__restrict__ x, const uint16_t *__restrict__ y,
+    const uint16_t *__restrict__ g, const uint16_t *__restrict__ gh,
+    const uint4 *__restrict__ Wp, int C, int M, int64_t T, float *__restrict__ u_raw,
+    float *__restrict__ sumsq, float *__restrict__ gH_res, float *__restrict__ gH_post,
+    float *__restrict__ gH_pre) {
+  using Cfg = ReduceCfg<N, NT>;
+  constexpr int D = N * N + 2 * N;
+  extern __shared__ uint4 lds[];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int r = lane & 15, q = lane >> 4;
+  const int64_t tw = static_cast<int64_t>(blockIdx.x) * 64 + wave * 16;
+  int64_t tl = tw + r;
+  if (tl > T - 1) tl = T - 1;
+  const uint16_t *xr = x + tl * N * C + q * 8;
+  const uint16_t *gr = g + tl * N * C + q * 8;
+  const uint16_t *yr = y + tl * C + q * 8;
+  const uint16_t *hr = gh + tl * C + q * 8;
+  const int ncs = C / 32;
+  const int sC = C / 32;   // K steps per stream
+
+  struct Tile { uint4 X[N], G[N], Y, H; };
+  Tile cur, nxt;
+  uint4 wst[Cfg::WV];
+  f32x4 acc[NT], ss = f32x4{0.f, 0.f, 0.f, 0.f};
+  float dots[D];
+#pragma unroll
+  for (int j = 0; j < NT; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int e = 0; e < D; ++e) dots[e] = 0.f;
+
+  auto load_tile = [&](Tile &tl_, int cs) {
+#pragma unroll
+    for (int j = 0; j < N; ++j) {
+      tl_.X[j] = *reinterpret_cast<const uint4 *>(xr + j * C + cs * 32);
+      tl_.G[j] = *reinterpret_cast<const uint4 *>(gr + j * C + cs * 32);
+    }
+    tl_.Y = *reinterpret_cast<const uint4 *>(yr + cs * 32);
+    tl_.H = *reinterpret_cast<const uint4 *>(hr + cs * 32);
+  };
+  auto load_w = [&](int cs) {
+#pragma unroll
+    for (int i = 0; i < Cfg::WV; ++i) {
+      const int e = i * 256 + threadIdx.x;
+      if (e < Cfg::kStageVec) {
+        const int j = e / (NT * 128), rem = e % (NT * 128);
+        wst[i] = Wp[static_cast<size_t>(j * sC + cs) * (NT * 128) + rem];
+      }
+    }
+  };
+  auto store_w = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < Cfg::WV; ++i) {
+      const int e = i * 256 + threadIdx.x;
+      if (e < Cfg::kStageVec) lds[buf * Cfg::kStageVec + e] = wst[i];
+    }
+  };
+  auto compute = [&](const Tile &tl_, int buf) {
+    const uint4 *wb = lds + buf * Cfg::kStageVec;
+#pragma unroll
+    for (int j = 0; j < N; ++j) {
+#pragma unroll
+      for (int jt = 0; jt < NT; ++jt) {
+        acc[jt] = mfma16(tl_.X[j], wb[((j * NT + jt) * 2 + 0) * 64 + lane], acc[jt]);
+        acc[jt] = mfma16(tl_.X[j], wb[((j * NT + jt) * 2 + 1) * 64 + lane], acc[jt]);
+      }
+      ss = mfma16(tl_.X[j], tl_.X[j], ss);
+    }
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+#pragma unroll
+      for (int j = 0; j < N; ++j) dots[i * N + j] = dot8_bf16(tl_.G[i], tl_.X[j], dots[i * N + j]);
+      dots[N * N + i] = dot8_bf16(tl_.G[i], tl_.Y, dots[N * N + i]);
+      dots[N * N + N + i] = dot8_bf16(tl_.H, tl_.X[i], dots[N * N + N + i]);
+    }
+  };
+
+  load_tile(cur, 0);
+  load_w(0);
+  store_w(0);
+  __syncthreads();
+  for (int cs = 0; cs < ncs; ++cs) {
+    const bool more = cs + 1 < ncs;
+    if (more) { load_tile(nxt, cs + 1); load_w(cs + 1); }
+    compute(cur, cs & 1);
+    if (more) store_w((cs + 1) & 1);
+    __syncthreads();
+    if (more) cur = nxt;
+  }
+
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int64_t t = tw + 4 * q + i;
+    if (t < T) {
+#pragma unroll
+      for (int jt = 0; jt < NT; ++jt) {
+        const int col = 16 * jt + r;
+        if (col < M) u_raw[t * M + col] = acc[jt][i];
+      }
+    }
+  }
+  const int64_t t = tw + r;
+  if ((r >> 2) == q) {
+    const int i = r & 3;
+    const float v = i == 0 ? ss[0] : (i == 1 ? ss[1] : (i == 2 ? ss[2] : ss[3]));
+    if (t < T) sumsq[t] = v;
+  }
+  // the four lanes (q = 0..3) of a token hold disjoint column subsets
+#pragma unroll
+  for (int e = 0; e < D; ++e) {
+    dots[e] += __shfl_xor(dots[e], 16, 64);
+    dots[e] += __shfl_xor(dots[e], 32, 64);
+  }
+  if (q == 0 && t < T) {
+#pragma unroll
+    for (int e = 0; e < N * N; ++e) gH_res[t * N * N + e] = dots[e];
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+      gH_post[t * N + i] = dots[N * N + i];
+      gH_pre[t * N + i] = dots[N * N + N + i];
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Per-token stage between the two backward passes: coefficients (recomputed),
+// g_z, and the operands pass 2 needs, in the layouts its MFMAs read:
+//   cpk  [T][CP] f32 : H_res (N*N) | H_pre (N) | H_post (N) | coefx
+//   vr   [Tpad][MP32] bf16 hi, lo : vr = r alpha g_z, row per token
+//   vrT  [Tpad/32][MP16][32] bf16 hi, lo : the same, tokens innermost
+//   gz   [T][M+3] f32 : g_z and the per-group sums of g_z u (for g_b, g_alpha)
+// Tokens T..Tpad-1 get zero vr so that padded tiles add nothing to g_W.
+template <int N, int MODE>
+__global__ __launch_bounds__(128) void bwd_epilogue_fast_kernel(
+    const float *__restrict__ u_raw, const float *__restrict__ sumsq, const float *__restrict__ b,
+    const float *__restrict__ alpha, const float *__restrict__ gH_res,
+    const float *__restrict__ gH_pre, const float *__restrict__ gH_post, int nC, float eps,
+    int sk_iters, int64_t T, int64_t Tpad, int CP, int MP32, int MP16, float *__restrict__ cpk,
+    uint16_t *__restrict__ vr_hi, uint16_t *__restrict__ vr_lo, uint16_t *__restrict__ vrT_hi,
+    uint16_t *__restrict__ vrT_lo, float *__restrict__ gz_out) {
+  constexpr int R = Dims<N, MODE>::R, M = Dims<N, MODE>::M;
+  const int64_t t = static_cast<int64_t>(blockIdx.x) * 128 + threadIdx.x;
+  if (t >= Tpad) return;
+  const int64_t blk = t >> 5;
+  const int tin = static_cast<int>(t & 31);
+  if (t >= T) {
+    for (int m = 0; m < MP32; ++m) { vr_hi[t * MP32 + m] = 0; vr_lo[t * MP32 + m] = 0; }
+    for (int m = 0; m < MP16; ++m) {
+      vrT_hi[(blk * MP16 + m) * 32 + tin] = 0;
+      vrT_lo[(blk * MP16 + m) * 32 + tin] = 0;
+    }
+    return;
+  }
+  float u[M], bb[M], a[R], Hr[N * N], Hp[N], Hq[N], gz[M];
+  float gr[N * N], gp[N], gq[N];
+  float sums[(MODE == MHCL_RES_SK) ? 2 * kMaxSkIters * N : 1];
+#pragma unroll
+  for (int m = 0; m < M; ++m) { u[m] = u_raw[t * M + m]; bb[m] = b[m]; }
+#pragma unroll
+  for (int e = 0; e < N * N; ++e) gr[e] = gH_res[t * N * N + e];
+#pragma unroll
+  for (int j = 0; j < N; ++j) { gp[j] = gH_pre[t * N + j]; gq[j] = gH_post[t * N + j]; }
+  const TokenParams p{alpha[0], alpha[1], alpha[2], eps, sk_iters};
+  const float r = token_coeffs<N, MODE>(u, sumsq[t], nC, bb, p, Hr, Hp, Hq, a,
+                                        (MODE == MHCL_RES_SK) ? sums : nullptr);
+  float *cp = cpk + t * CP;
+#pragma unroll
+  for (int e = 0; e < N * N; ++e) cp[e] = Hr[e];
+#pragma unroll
+  for (int j = 0; j < N; ++j) { cp[N * N + j] = Hp[j]; cp[N * N + N + j] = Hq[j]; }
+  token_coeffs_bwd<N, MODE>(gr, gp, gq, a, Hr, Hp, Hq, sums, sk_iters, gz);
+  float ga[3] = {0.f, 0.f, 0.f}, dot = 0.f;
+#pragma unroll
+  for (int m = 0; m < M; ++m) {
+    const int g = m < R ? 0 : (m < R + N ? 1 : 2);
+    const float al = g == 0 ? p.alpha_res : (g == 1 ? p.alpha_pre : p.alpha_post);
+    const float vr = r * al * gz[m];
+    gz_out[t * (M + 3) + m] = gz[m];
+    ga[g] += gz[m] * (r * u[m]);
+    dot += vr * u[m];
+    uint16_t hi, lo;
+    split_bf16(vr, hi, lo);
+    vr_hi[t * MP32 + m] = hi;
+    vr_lo[t * MP32 + m] = lo;
+    vrT_hi[(blk * MP16 + m) * 32 + tin] = hi;
+    vrT_lo[(blk * MP16 + m) * 32 + tin] = lo;
+  }
+  for (int m = M; m < MP32; ++m) { vr_hi[t * MP32 + m] = 0; vr_lo[t * MP32 + m] = 0; }
+  for (int m = M; m < MP16; ++m) {
+    vrT_hi[(blk * MP16 + m) * 32 + tin] = 0;
+    vrT_lo[(blk * MP16 + m) * 32 + tin] = 0;
+  }
+#pragma unroll
+  for (int g = 0; g < 3; ++g) gz_out[t * (M + 3) + M + g] = ga[g];
+  cp[N * N + 2 * N] = (r * r / static_cast<float>(nC)) * dot;
+}
+
+// ---------------------------------------------------------------------------
+// Backward pass 2a: the stream outputs.
+//   g_x[j] = sum_i H_res[i][j] g_xout[i] + H_pre[j] g_h + (W vr)[j] - x[j] coefx
+//   g_y    = sum_i H_post[i] g_xout[i]
+// summed in fp32 and rounded to bf16 once.  A wave owns one 32-column step of C
+// (all n streams) and walks a chunk of tokens 16 at a time; its slice of W (A
+// layout, hi + lo) stays in registers for the whole walk.  (W vr) comes out of
+// the MFMA already in the lane order of the stream loads: lane (token, q) gets
+// the 8 columns it also loaded.
+template <int N>
+__global__ __launch_bounds__(256, 2) void bwd_out_kernel(
+    const uint16_t *__restrict__ x, const uint16_t *__restrict__ g,
+    const uint16_t *__restrict__ gh, const uint4 *__restrict__ Wa, const float *__restrict__ cpk,
+    const uint16_t *__restrict__ vr_hi, const uint16_t *__restrict__ vr_lo, int C, int64_t T,
+    int tokens_per_block, int CP, uint16_t *__restrict__ g_x, uint16_t *__restrict__ g_y) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int r = lane & 15, q = lane >> 4;
+  const int cs = blockIdx.x * 4 + wave;            // column step of this wave
+  if (cs >= C / 32) return;
+  const int c0 = cs * 32 + q * 8;
+  const int sC = C / 32;
+  uint4 wa[N][2][2];
+#pragma unroll
+  for (int j = 0; j < N; ++j)
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+      for (int p = 0; p < 2; ++p)
+        wa[j][h][p] = Wa[(static_cast<size_t>((j * sC + cs) * 2 + h) * 2 + p) * 64 + lane];
+
+  const int64_t tb = static_cast<int64_t>(blockIdx.y) * tokens_per_block;
+  int64_t te = tb + tokens_per_block;
+  if (te > T) te = T;
+  for (int64_t t0 = tb; t0 < te; t0 += 16) {
+    const int64_t t = t0 + r;
+    const bool live = t < te;
+    const int64_t tl = live ? t : te - 1;
+    uint4 X[N], G[N], H;
+#pragma unroll
+    for (int j = 0; j < N; ++j) {
+      X[j] = *reinterpret_cast<const uint4 *>(x + (tl * N + j) * C + c0);
+      G[j] = *reinterpret_cast<const uint4 *>(g + (tl * N + j) * C + c0);
+    }
+    H = *reinterpret_cast<const uint4 *>(gh + tl * C + c0);
+    const uint4 vbh = *reinterpret_cast<const uint4 *>(vr_hi + tl * 32 + q * 8);
+    const uint4 vbl = *reinterpret_cast<const uint4 *>(vr_lo + tl * 32 + q * 8);
+    float cp[N * N + 2 * N + 1];
+    const float *cpp = cpk + tl * CP;
+#pragma unroll
+    for (int e = 0; e < N * N + 2 * N + 1; ++e) cp[e] = cpp[e];
+
+    float gv[N][8], hv[8];
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+      gv[i][0] = bf16lo(G[i].x); gv[i][1] = bf16hi(G[i].x); gv[i][2] = bf16lo(G[i].y);
+      gv[i][3] = bf16hi(G[i].y); gv[i][4] = bf16lo(G[i].z); gv[i][5] = bf16hi(G[i].z);
+      gv[i][6] = bf16lo(G[i].w); gv[i][7] = bf16hi(G[i].w);
+    }
+    hv[0] = bf16lo(H.x); hv[1] = bf16hi(H.x); hv[2] = bf16lo(H.y); hv[3] = bf16hi(H.y);
+    hv[4] = bf16lo(H.z); hv[5] = bf16hi(H.z); hv[6] = bf16lo(H.w); hv[7] = bf16hi(H.w);
+
+    {   // g_y
+      float o[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        float s = 0.f;
+#pragma unroll
+        for (int i = 0; i < N; ++i) s += cp[N * N + N + i] * gv[i][e];
+        o[e] = s;
+      }
+      if (live) {
+        uint4 ov;
+        ov.x = cvt_pk_bf16(o[0], o[1]); ov.y = cvt_pk_bf16(o[2], o[3]);
+        ov.z = cvt_pk_bf16(o[4], o[5]); ov.w = cvt_pk_bf16(o[6], o[7]);
+        *reinterpret_cast<uint4 *>(g_y + t * C + c0) = ov;
+      }
+    }
+    const float cx = cp[N * N + 2 * N];
+#pragma unroll
+    for (int j = 0; j < N; ++j) {
+      f32x4 wv[2];
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        wv[h] = mfma16(wa[j][h][0], vbh, f32x4{0.f, 0.f, 0.f, 0.f});
+        wv[h] = mfma16(wa[j][h][1], vbh, wv[h]);
+        wv[h] = mfma16(wa[j][h][0], vbl, wv[h]);
+      }
+      float xv[8], o[8];
+      xv[0] = bf16lo(X[j].x); xv[1] = bf16hi(X[j].x); xv[2] = bf16lo(X[j].y); xv[3] = bf16hi(X[j].y);
+      xv[4] = bf16lo(X[j].z); xv[5] = bf16hi(X[j].z); xv[6] = bf16lo(X[j].w); xv[7] = bf16hi(X[j].w);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        float s = wv[e >> 2][e & 3] - xv[e] * cx;
+#pragma unroll
+        for (int i = 0; i < N; ++i) s += cp[i * N + j] * gv[i][e];
+        s += cp[N * N + j] * hv[e];
+        o[e] = s;
+      }
+      if (live) {
+        uint4 ov;
+        ov.x = cvt_pk_bf16(o[0], o[1]); ov.y = cvt_pk_bf16(o[2], o[3]);
+        ov.z = cvt_pk_bf16(o[4], o[5]); ov.w = cvt_pk_bf16(o[6], o[7]);
+        *reinterpret_cast<uint4 *>(g_x + (t * N + j) * C + c0) = ov;
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Backward pass 2b: g_W[k][m] = sum_t x_hat[t][k] vr[t][m], the one reduction
+// over tokens.  A wave owns CSW K steps (32 rows of g_W each) and walks a chunk
+// of tokens 32 at a time.  x arrives with tokens across lanes, but the
+// contraction runs over tokens, so each x tile is first transposed by an MFMA
+// against a 0/1 selection matrix (exact: the values are bf16), which leaves
+// lane (k, q) holding 4 + 4 tokens of column k: the B operand of
+//   D[m][k] += vrT[m][token] * x^T[token][k].
+// Partial sums per token chunk go to `out`; they are added in chunk order.
+template <int NT, int CSW>
+__global__ __launch_bounds__(256, 2) void bwd_gw_kernel(
+    const uint16_t *__restrict__ x, const uint16_t *__restrict__ vrT_hi,
+    const uint16_t *__restrict__ vrT_lo, int K, int M, int MP16, int64_t T, int64_t nblk,
+    int blks_per_chunk, float *__restrict__ out) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int r = lane & 15, q = lane >> 4;
+  const int s0 = (blockIdx.x * 4 + wave) * CSW;     // first K step of this wave
+  const int nsteps = K / 32;
+  if (s0 >= nsteps) return;
+  // selection operands: column c of half h picks row 16 h + c
+  uint4 sel[2];
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    uint32_t w[4];
+#pragma unroll
+    for (int e2 = 0; e2 < 4; ++e2) {
+      const int k0 = 8 * q + 2 * e2, k1 = k0 + 1;
+      w[e2] = (k0 == 16 * h + r ? 0x3F80u : 0u) | (k1 == 16 * h + r ? 0x3F800000u : 0u);
+    }
+    sel[h] = uint4{w[0], w[1], w[2], w[3]};
+  }
+  f32x4 acc[CSW][2][NT];
+#pragma unroll
+  for (int c = 0; c < CSW; ++c)
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+      for (int mt = 0; mt < NT; ++mt) acc[c][h][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  const int64_t b0 = static_cast<int64_t>(blockIdx.y) * blks_per_chunk;
+  int64_t b1 = b0 + blks_per_chunk;
+  if (b1 > nblk) b1 = nblk;
+  for (int64_t blk = b0; blk < b1; ++blk) {
+    uint4 X[CSW][2];
+#pragma unroll
+    for (int gI = 0; gI < 2; ++gI) {
+      int64_t t = blk * 32 + gI * 16 + r;
+      if (t > T - 1) t = T - 1;
+#pragma unroll
+      for (int c = 0; c < CSW; ++c) {
+        const int s = s0 + c < nsteps ? s0 + c : nsteps - 1;
+        X[c][gI] = *reinterpret_cast<const uint4 *>(x + t * K + s * 32 + q * 8);
+      }
+    }
+    uint4 va[NT][2];
+#pragma unroll
+    for (int mt = 0; mt < NT; ++mt) {
+      const size_t row = (static_cast<size_t>(blk) * MP16 + mt * 16 + r) * 32;
+      const uint2 h0 = *reinterpret_cast<const uint2 *>(vrT_hi + row + 4 * q);
+      const uint2 h1 = *reinterpret_cast<const uint2 *>(vrT_hi + row + 16 + 4 * q);
+      const uint2 l0 = *reinterpret_cast<const uint2 *>(vrT_lo + row + 4 * q);
+      const uint2 l1 = *reinterpret_cast<const uint2 *>(vrT_lo + row + 16 + 4 * q);
+      va[mt][0] = uint4{h0.x, h0.y, h1.x, h1.y};
+      va[mt][1] = uint4{l0.x, l0.y, l1.x, l1.y};
+    }
+#pragma unroll
+    for (int c = 0; c < CSW; ++c) {
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const f32x4 z = f32x4{0.f, 0.f, 0.f, 0.f};
+        const f32x4 t0 = mfma16(X[c][0], sel[h], z);   // tokens 4q+i of the first 16
+        const f32x4 t1 = mfma16(X[c][1], sel[h], z);   // tokens 4q+i of the second 16
+        uint4 bt;
+        bt.x = cvt_pk_bf16(t0[0], t0[1]); bt.y = cvt_pk_bf16(t0[2], t0[3]);
+        bt.z = cvt_pk_bf16(t1[0], t1[1]); bt.w = cvt_pk_bf16(t1[2], t1[3]);
+#pragma unroll
+        for (int mt = 0; mt < NT; ++mt) {
+          acc[c][h][mt] = mfma16(va[mt][0], bt, acc[c][h][mt]);
+          acc[c][h][mt] = mfma16(va[mt][1], bt, acc[c][h][mt]);
+        }
+      }
+    }
+  }
+  float *dst = out + static_cast<size_t>(blockIdx.y) * K * M;
+#pragma unroll
+  for (int c = 0; c < CSW; ++c) {
+    if (s0 + c < nsteps) {
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const int k = (s0 + c) * 32 + 16 * h + r;
+#pragma unroll
+        for (int mt = 0; mt < NT; ++mt)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const int m = mt * 16 + 4 * q + i;
+            if (m < M) dst[static_cast<size_t>(k) * M + m] = acc[c][h][mt][i];
+          }
+      }
+    }
+  }
+}
+
+template <typename F>
+hipError_t dispatch_nt(int NT, F &&f) {
+  switch (NT) {
+    case 1: return f(std::integral_constant<int, 1>{});
+    case 2: return f(std::integral_constant<int, 2>{});
+    case 3: return f(std::integral_constant<int, 3>{});
+    case 9: return f(std::integral_constant<int, 9>{});
+  }
+  return hipErrorInvalidValue;
+}
+
+}  // namespace
+
+bool fast_path_ok(const mhcl_desc &d) {
+  if (d.io_dtype != MHCL_BF16 || d.C % 64 != 0) return false;
+  const int NT = logit_tiles(res_logits(d.n, d.res_mode) + 2 * d.n);
+  return NT == 1 || NT == 2 || NT == 3 || NT == 9;
+}
+
+size_t packed_w_b_bytes(const mhcl_desc &d, int M) { return packed_b_bytes(d.n * d.C, M); }
+
+hipError_t launch_pack_w_b(const mhcl_desc &d, int M, const float *W, void *Wp, hipStream_t s) {
+  const int K = d.n * d.C, NT = logit_tiles(M);
+  const int threads = (K / 32) * NT * 64;
+  hipLaunchKernelGGL(pack_w_b_kernel, dim3((threads + 255) / 256), dim3(256), 0, s, W, K, M, NT,
+                     static_cast<uint4 *>(Wp));
+  return hipGetLastError();
+}
+
+hipError_t launch_proj_mfma(const mhcl_desc &d, int M, const void *x, const void *Wp, float *u_raw,
+                            float *sumsq, hipStream_t s) {
+  const int K = d.n * d.C;
+  return dispatch_nt(logit_tiles(M), [&](auto nt) {
+    constexpr int NT = decltype(nt)::value;
+    auto kern = proj_mfma_kernel<NT>;
+    constexpr int lds = ProjCfg<NT>::kLdsBytes;
+    if (lds > 64 * 1024) {
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+      if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>((d.T + 127) / 128)), dim3(256), lds, s,
+                       static_cast<const uint16_t *>(x), static_cast<const uint4 *>(Wp), K, M, d.T,
+                       u_raw, sumsq);
+    return hipGetLastError();
+  });
+}
+
+
+// ---- fused backward, bf16, n <= 4 -------------------------------------------
+bool fast_bwd_ok(const mhcl_desc &d) { return fast_path_ok(d) && d.n <= 4; }
+
+namespace {
+int gw_xblocks(const mhcl_desc &d) { return (d.n * d.C / 32 + 15) / 16; }   // 4 waves x 4 K steps
+}  // namespace
+
+int gw_chunks_fast(const mhcl_desc &d) {
+  const int64_t nblk = (d.T + 31) / 32;
+  int64_t c = (512 + gw_xblocks(d) - 1) / gw_xblocks(d);
+  if (c > 64) c = 64;
+  if (c > nblk) c = nblk;
+  if (c < 1) c = 1;
+  return static_cast<int>(c);
+}
+
+FastBwdWs::FastBwdWs(const mhcl_desc &d, void *ws) {
+  WsCursor c(ws);
+  const size_t T = static_cast<size_t>(d.T), Tpad = (T + 31) / 32 * 32;
+  const int n = d.n, M = res_logits(d.n, d.res_mode) + 2 * d.n, K = d.n * d.C;
+  CP = 32;
+  MP32 = logit_steps(M) * 32;
+  MP16 = logit_tiles(M) * 16;
+  u_raw = c.take<float>(T * M);
+  sumsq = c.take<float>(T);
+  gH_res = c.take<float>(T * n * n);
+  gH_pre = c.take<float>(T * n);
+  gH_post = c.take<float>(T * n);
+  cpk = c.take<float>(T * CP);
+  gz = c.take<float>(T * (M + 3));
+  vr_hi = c.take<uint16_t>(Tpad * MP32);
+  vr_lo = c.take<uint16_t>(Tpad * MP32);
+  vrT_hi = c.take<uint16_t>(Tpad * MP16);
+  vrT_lo = c.take<uint16_t>(Tpad * MP16);
+  Wp = c.take<char>(packed_b_bytes(K, M));
+  Wa = c.take<char>(packed_a_bytes(K, M));
+  partials = c.take<float>(static_cast<size_t>(gw_chunks_fast(d)) * K * M);
+  bytes = c.off;
+}
+
+hipError_t launch_pack_w_a(const mhcl_desc &d, int M, const float *W, void *Wa, hipStream_t s) {
+  const int K = d.n * d.C, MS = logit_steps(M);
+  const int threads = (K / 32) * 2 * MS * 64;
+  hipLaunchKernelGGL(pack_w_a_kernel, dim3((threads + 255) / 256), dim3(256), 0, s, W, K, M, MS,
+                     static_cast<uint4 *>(Wa));
+  return hipGetLastError();
+}
+
+hipError_t launch_bwd_reduce(const mhcl_desc &d, int M, const void *x, const void *y,
+                             const void *g_xout, const void *g_h, const FastBwdWs &w,
+                             hipStream_t s) {
+  auto go = [&](auto nn, auto nt) {
+    constexpr int N = decltype(nn)::value, NT = decltype(nt)::value;
+    auto kern = bwd_reduce_kernel<N, NT>;
+    hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>((d.T + 63) / 64)), dim3(256),
+                       (ReduceCfg<N, NT>::kLdsBytes), s, static_cast<const uint16_t *>(x),
+                       static_cast<const uint16_t *>(y), static_cast<const uint16_t *>(g_xout),
+                       static_cast<const uint16_t *>(g_h), reinterpret_cast<const uint4 *>(w.Wp),
+                       d.C, M, d.T, w.u_raw, w.sumsq, w.gH_res, w.gH_post, w.gH_pre);
+    return hipGetLastError();
+  };
+  const int NT = logit_tiles(M);
+  using I1 = std::integral_constant<int, 1>;
+  using I2 = std::integral_constant<int, 2>;
+  using I3 = std::integral_constant<int, 3>;
+  using I4 = std::integral_constant<int, 4>;
+  switch (d.n * 10 + NT) {   // the (n, logit tiles) pairs that occur for n <= 4
+    case 11: return go(I1{}, I1{});   // lite M=3, SK M=3
+    case 21: return go(I2{}, I1{});   // lite M=6, SK M=8
+    case 31: return go(I3{}, I1{});   // lite M=12, SK M=15
+    case 42: return go(I4{}, I2{});   // lite M=32, SK M=24
+  }
+  return hipErrorInvalidValue;
+}
+
+hipError_t launch_bwd_epilogue_fast(const mhcl_desc &d, const float *b, const float *alpha,
+                                    const FastBwdWs &w, hipStream_t s) {
+  const int64_t Tpad = (d.T + 31) / 32 * 32;
+  auto go = [&](auto nn, auto mm) {
+    constexpr int N = decltype(nn)::value, MODE = decltype(mm)::value;
+    hipLaunchKernelGGL((bwd_epilogue_fast_kernel<N, MODE>),
+                       dim3(static_cast<unsigned>((Tpad + 127) / 128)), dim3(128), 0, s, w.u_raw,
+                       w.sumsq, b, alpha, w.gH_res, w.gH_pre, w.gH_post, d.n * d.C, d.eps,
+                       d.sk_iters, d.T, Tpad, w.CP, w.MP32, w.MP16, w.cpk, w.vr_hi, w.vr_lo,
+                       w.vrT_hi, w.vrT_lo, w.gz);
+    return hipGetLastError();
+  };
+  using L = std::integral_constant<int, MHCL_RES_LITE>;
+  using S = std::integral_constant<int, MHCL_RES_SK>;
+  const bool lite = d.res_mode == MHCL_RES_LITE;
+  switch (d.n) {
+    case 1: return lite ? go(std::integral_constant<int, 1>{}, L{}) : go(std::integral_constant<int, 1>{}, S{});
+    case 2: return lite ? go(std::integral_constant<int, 2>{}, L{}) : go(std::integral_constant<int, 2>{}, S{});
+    case 3: return lite ? go(std::integral_constant<int, 3>{}, L{}) : go(std::integral_constant<int, 3>{}, S{});
+    case 4: return lite ? go(std::integral_constant<int, 4>{}, L{}) : go(std::integral_constant<int, 4>{}, S{});
+  }
+  return hipErrorInvalidValue;
+}
+
+hipError_t launch_bwd_out(const mhcl_desc &d, const void *x, const void *g_xout, const void *g_h,
+                          const FastBwdWs &w, void *g_x, void *g_y, hipStream_t s) {
+  constexpr int kTokensPerBlock = 512;
+  auto go = [&](auto nn) {
+    constexpr int N = decltype(nn)::value;
+    const dim3 grid((d.C / 32 + 3) / 4, static_cast<unsigned>((d.T + kTokensPerBlock - 1) / kTokensPerBlock));
+    hipLaunchKernelGGL(bwd_out_kernel<N>, grid, dim3(256), 0, s, static_cast<const uint16_t *>(x),
+                       static_cast<const uint16_t *>(g_xout), static_cast<const uint16_t *>(g_h),
+                       reinterpret_cast<const uint4 *>(w.Wa), w.cpk, w.vr_hi, w.vr_lo, d.C, d.T,
+                       kTokensPerBlock, w.CP, static_cast<uint16_t *>(g_x),
+                       static_cast<uint16_t *>(g_y));
+    return hipGetLastError();
+  };
+  switch (d.n) {
+    case 1: return go(std::integral_constant<int, 1>{});
+    case 2: return go(std::integral_constant<int, 2>{});
+    case 3: return go(std::integral_constant<int, 3>{});
+    case 4: return go(std::integral_constant<int, 4>{});
+  }
+  return hipErrorInvalidValue;
+}
+
+hipError_t launch_bwd_gw(const mhcl_desc &d, int M, const void *x, const FastBwdWs &w, float *g_W,
+                         hipStream_t s) {
+  const int K = d.n * d.C;
+  const int64_t nblk = (d.T + 31) / 32;
+  const int chunks = gw_chunks_fast(d);
+  const int bpc = static_cast<int>((nblk + chunks - 1) / chunks);
+  float *dst = chunks == 1 ? g_W : w.partials;
+  hipError_t e = dispatch_nt(logit_tiles(M), [&](auto nt) {
+    constexpr int NT = decltype(nt)::value;
+    if constexpr (NT <= 3) {
+      hipLaunchKernelGGL((bwd_gw_kernel<NT, 4>), dim3(gw_xblocks(d), chunks), dim3(256), 0, s,
+                         static_cast<const uint16_t *>(x), w.vrT_hi, w.vrT_lo, K, M, w.MP16, d.T,
+                         nblk, bpc, dst);
+      return hipGetLastError();
+    } else {
+      return hipErrorInvalidValue;
+    }
+  });
+  if (e != hipSuccess || chunks == 1) return e;
+  return launch_sum_partials(w.partials, static_cast<size_t>(K) * M, chunks, g_W, s);
+}
+
+}  // namespace mhcl

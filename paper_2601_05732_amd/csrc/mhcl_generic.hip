@@ -495,6 +495,14 @@ __global__ __launch_bounds__(kBlock) void fill_zero_kernel(float *__restrict__ p
   if (i < count) p[i] = 0.f;
 }
 
+// 16 bytes per thread and iteration, grid-stride
+__global__ __launch_bounds__(kBlock) void copy_kernel(uint4 *__restrict__ dst,
+                                                      const uint4 *__restrict__ src, size_t n16) {
+  for (size_t i = static_cast<size_t>(blockIdx.x) * kBlock + threadIdx.x; i < n16;
+       i += static_cast<size_t>(gridDim.x) * kBlock)
+    dst[i] = src[i];
+}
+
 inline unsigned blocks_for(int64_t items, int per) {
   return static_cast<unsigned>((items + per - 1) / per);
 }
@@ -668,6 +676,23 @@ hipError_t launch_gw_generic(const mhcl_desc &d, int M, const void *x, const flo
                        (const float *)partials, size, chunks, g_W);
     return hipGetLastError();
   });
+}
+
+hipError_t launch_sum_partials(const float *partials, size_t size, int chunks, float *out,
+                               hipStream_t s) {
+  hipLaunchKernelGGL(sum_partials_kernel, dim3(blocks_for(size, kBlock)), dim3(kBlock), 0, s,
+                     partials, size, chunks, out);
+  return hipGetLastError();
+}
+
+hipError_t launch_copy(void *dst, const void *src, size_t bytes, hipStream_t s) {
+  const size_t n16 = bytes / 16;
+  if (n16 == 0) return hipSuccess;
+  size_t blocks = (n16 + kBlock - 1) / kBlock;
+  if (blocks > 256 * 32) blocks = 256 * 32;
+  hipLaunchKernelGGL(copy_kernel, dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0, s,
+                     static_cast<uint4 *>(dst), static_cast<const uint4 *>(src), n16);
+  return hipGetLastError();
 }
 
 hipError_t launch_fill_zero(float *p, size_t count, hipStream_t s) {

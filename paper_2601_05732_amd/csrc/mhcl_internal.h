@@ -65,6 +65,7 @@ hipError_t launch_gx_generic(const mhcl_desc &d, int M, bool fused, const void *
 int gw_chunks_generic(const mhcl_desc &d);
 hipError_t launch_gw_generic(const mhcl_desc &d, int M, const void *x, const float *vr,
                              float *partials, float *g_W, hipStream_t s);
+hipError_t launch_copy(void *dst, const void *src, size_t bytes, hipStream_t s);
 // a fill kernel (safe under graph capture, unlike a memset node)
 hipError_t launch_fill_zero(float *p, size_t count, hipStream_t s);
 // dst[c] = sum_t src[t*ld + c], c < cols, fixed order
@@ -72,5 +73,37 @@ hipError_t launch_colsum(const float *src, int64_t T, int ld, int cols, float *d
 // g_b [M] and g_alpha [3] from gz [T, M+3]
 hipError_t launch_param_sums(const mhcl_desc &d, int M, const float *gz, float *g_b, float *g_alpha,
                              hipStream_t s);
+
+
+// ---- bf16 fast path (MFMA projections); needs fast_path_ok(desc) ---------
+bool fast_path_ok(const mhcl_desc &d);
+size_t packed_w_b_bytes(const mhcl_desc &d, int M);
+hipError_t launch_pack_w_b(const mhcl_desc &d, int M, const float *W, void *Wp, hipStream_t s);
+hipError_t launch_proj_mfma(const mhcl_desc &d, int M, const void *x, const void *Wp, float *u_raw,
+                            float *sumsq, hipStream_t s);
+
+// fused backward on the fast path (needs fast_bwd_ok(desc))
+bool fast_bwd_ok(const mhcl_desc &d);
+int gw_chunks_fast(const mhcl_desc &d);
+struct FastBwdWs {
+  float *u_raw, *sumsq, *gH_res, *gH_pre, *gH_post, *cpk, *gz, *partials;
+  uint16_t *vr_hi, *vr_lo, *vrT_hi, *vrT_lo;
+  char *Wp, *Wa;
+  int CP, MP32, MP16;
+  size_t bytes;
+  FastBwdWs(const mhcl_desc &d, void *ws);
+};
+hipError_t launch_pack_w_a(const mhcl_desc &d, int M, const float *W, void *Wa, hipStream_t s);
+hipError_t launch_bwd_reduce(const mhcl_desc &d, int M, const void *x, const void *y,
+                             const void *g_xout, const void *g_h, const FastBwdWs &w,
+                             hipStream_t s);
+hipError_t launch_bwd_epilogue_fast(const mhcl_desc &d, const float *b, const float *alpha,
+                                    const FastBwdWs &w, hipStream_t s);
+hipError_t launch_bwd_out(const mhcl_desc &d, const void *x, const void *g_xout, const void *g_h,
+                          const FastBwdWs &w, void *g_x, void *g_y, hipStream_t s);
+hipError_t launch_bwd_gw(const mhcl_desc &d, int M, const void *x, const FastBwdWs &w, float *g_W,
+                         hipStream_t s);
+hipError_t launch_sum_partials(const float *partials, size_t size, int chunks, float *out,
+                               hipStream_t s);
 
 }  // namespace mhcl
