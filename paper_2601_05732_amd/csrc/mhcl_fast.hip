@@ -54,19 +54,19 @@ __global__ __launch_bounds__(256) void pack_w_b_kernel(const float *__restrict__
 template <int NT>
 struct ProjCfg {
   static constexpr int KC = NT <= 2 ? 8 : (NT == 3 ? 4 : 2);   // K steps per chunk
-  static constexpr int kChunkVec = KC * NT * 2 * 64;           // uint4 per chunk
+  static constexpr int kChunkVec = KC * NT * 2 * 64;           // u32x4 per chunk
   static constexpr int kLdsBytes = 2 * kChunkVec * 16;
 };
 
 template <int NT>
 __global__ __launch_bounds__(256, 2) void proj_mfma_kernel(const uint16_t *__restrict__ x,
-                                                           const uint4 *__restrict__ Wp, int K,
+                                                           const u32x4 *__restrict__ Wp, int K,
                                                            int M, int64_t T,
                                                            float *__restrict__ u_raw,
                                                            float *__restrict__ sumsq) {
   using Cfg = ProjCfg<NT>;
   constexpr int KC = Cfg::KC, TG = 2;
-  extern __shared__ uint4 lds[];
+  extern __shared__ u32x4 lds[];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int r = lane & 15, q = lane >> 4;
   const int64_t tw = static_cast<int64_t>(blockIdx.x) * 128 + wave * 32;
@@ -88,69 +88,86 @@ __global__ __launch_bounds__(256, 2) void proj_mfma_kernel(const uint16_t *__res
     for (int j = 0; j < NT; ++j) acc[g][j] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
 
-  constexpr int WV = Cfg::kChunkVec / 256;   // uint4 of W each thread stages per chunk
-  uint4 a[2][TG][KC], wst[WV];
+  constexpr int WV = Cfg::kChunkVec / 256;   // u32x4 of W each thread stages per chunk
+  u32x4 a[2][TG][KC], wst[WV];
+  const int wlim = nsteps * NT * 2 * 64 - 1;   // last valid u32x4 of packed W
 
-  auto load_a = [&](uint4 (&dst)[TG][KC], int c) {
+  // Loads never branch: a step past the end re-reads the last step (address
+  // clamped); compute() zeroes such a tile where it is consumed, so it adds
+  // nothing and the load itself is never waited for early.
+  auto load_a = [&](u32x4 (&dst)[TG][KC], int c) {
 #pragma unroll
     for (int s = 0; s < KC; ++s) {
       const int step = c * KC + s;
-      if (step < nsteps) {
+      const int sc = step < nsteps ? step : nsteps - 1;
 #pragma unroll
-        for (int g = 0; g < TG; ++g)
-          dst[g][s] = *reinterpret_cast<const uint4 *>(row[g] + step * 32);
-      }
+      for (int g = 0; g < TG; ++g) dst[g][s] = *reinterpret_cast<const u32x4 *>(row[g] + sc * 32);
     }
   };
   auto load_w = [&](int c) {
-    const size_t base = static_cast<size_t>(c) * Cfg::kChunkVec;
-    const size_t lim = static_cast<size_t>(nsteps) * NT * 2 * 64;
+    const int base = c * Cfg::kChunkVec;
 #pragma unroll
     for (int i = 0; i < WV; ++i) {
-      const size_t e = base + i * 256 + threadIdx.x;
-      wst[i] = e < lim ? Wp[e] : uint4{0, 0, 0, 0};
+      const int e = base + i * 256 + threadIdx.x;
+      wst[i] = Wp[e < wlim ? e : wlim];
     }
   };
   auto store_w = [&](int buf) {
 #pragma unroll
     for (int i = 0; i < WV; ++i) lds[buf * Cfg::kChunkVec + i * 256 + threadIdx.x] = wst[i];
   };
-  auto compute = [&](const uint4 (&av)[TG][KC], int buf, int c) {
-    const uint4 *wb = lds + buf * Cfg::kChunkVec;
+  auto compute = [&](const u32x4 (&av)[TG][KC], int buf, int c) {
+    const u32x4 *wb = lds + buf * Cfg::kChunkVec;
 #pragma unroll
     for (int s = 0; s < KC; ++s) {
-      if (c * KC + s < nsteps) {
+      const bool valid = c * KC + s < nsteps;
+      u32x4 at[TG];
 #pragma unroll
-        for (int j = 0; j < NT; ++j) {
-          const uint4 bh = wb[((s * NT + j) * 2 + 0) * 64 + lane];
-          const uint4 bl = wb[((s * NT + j) * 2 + 1) * 64 + lane];
+      for (int g = 0; g < TG; ++g) at[g] = valid ? av[g][s] : u32x4{0, 0, 0, 0};
 #pragma unroll
-          for (int g = 0; g < TG; ++g) {
-            acc[g][j] = mfma16(av[g][s], bh, acc[g][j]);
-            acc[g][j] = mfma16(av[g][s], bl, acc[g][j]);
-          }
+      for (int j = 0; j < NT; ++j) {
+        const u32x4 bh = wb[((s * NT + j) * 2 + 0) * 64 + lane];
+        const u32x4 bl = wb[((s * NT + j) * 2 + 1) * 64 + lane];
+#pragma unroll
+        for (int g = 0; g < TG; ++g) {
+          acc[g][j] = mfma16(at[g], bh, acc[g][j]);
+          acc[g][j] = mfma16(at[g], bl, acc[g][j]);
         }
-#pragma unroll
-        for (int g = 0; g < TG; ++g) ss[g] = mfma16(av[g][s], av[g][s], ss[g]);
       }
+#pragma unroll
+      for (int g = 0; g < TG; ++g) ss[g] = mfma16(at[g], at[g], ss[g]);
     }
   };
 
-  load_a(a[0], 0);
+  // W is requested before the A tiles of the same chunk: loads return in order,
+  // so staging W into LDS only has to wait for the W loads and leaves the A
+  // loads of the next chunk in flight across the barrier.
   load_w(0);
+  load_a(a[0], 0);
   store_w(0);
   __syncthreads();
-  for (int c = 0; c < nchunks; c += 2) {
-    if (c + 1 < nchunks) { load_a(a[1], c + 1); load_w(c + 1); }
+  int c = 0;
+  for (; c + 2 < nchunks; c += 2) {
+    load_w(c + 1); load_a(a[1], c + 1);
+    __builtin_amdgcn_sched_barrier(0);   // keep the whole next chunk in flight during compute
     compute(a[0], 0, c);
-    if (c + 1 < nchunks) store_w(1);
+    store_w(1);
     __syncthreads();
-    if (c + 1 < nchunks) {
-      if (c + 2 < nchunks) { load_a(a[0], c + 2); load_w(c + 2); }
-      compute(a[1], 1, c + 1);
-      if (c + 2 < nchunks) store_w(0);
-      __syncthreads();
-    }
+    load_w(c + 2); load_a(a[0], c + 2);
+    __builtin_amdgcn_sched_barrier(0);
+    compute(a[1], 1, c + 1);
+    store_w(0);
+    __syncthreads();
+  }
+  if (c + 1 < nchunks) {
+    load_w(c + 1); load_a(a[1], c + 1);
+    __builtin_amdgcn_sched_barrier(0);
+    compute(a[0], 0, c);
+    store_w(1);
+    __syncthreads();
+    compute(a[1], 1, c + 1);
+  } else {
+    compute(a[0], 0, c);
   }
 
   // D layout: lane (r, q) holds logit 16 j + r for tokens 4 q + i
@@ -204,11 +221,17 @@ __global__ __launch_bounds__(256) void pack_w_a_kernel(const float *__restrict__
 }
 
 // sum over 8 bf16 pairs-of-products: acc + <a, b>, products exact, fp32 sums
-__device__ __forceinline__ float dot8_bf16(const uint4 &a, const uint4 &b, float acc) {
-  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a.x), __builtin_bit_cast(bf16x2, b.x), acc, false);
-  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a.y), __builtin_bit_cast(bf16x2, b.y), acc, false);
-  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a.z), __builtin_bit_cast(bf16x2, b.z), acc, false);
-  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a.w), __builtin_bit_cast(bf16x2, b.w), acc, false);
+__device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float acc) {
+  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a), __builtin_bit_cast(bf16x2, b),
+                                         acc, false);
+}
+// (the words are passed by value: a bit cast applied directly to a vector
+// element expression reads element 0 whatever the index)
+__device__ __forceinline__ float dot8_bf16(const u32x4 &a, const u32x4 &b, float acc) {
+  acc = dot2_bf16(a.x, b.x, acc);
+  acc = dot2_bf16(a.y, b.y, acc);
+  acc = dot2_bf16(a.z, b.z, acc);
+  acc = dot2_bf16(a.w, b.w, acc);
   return acc;
 }
 
@@ -225,7 +248,7 @@ __device__ __forceinline__ float dot8_bf16(const uint4 &a, const uint4 &b, float
 // v_dot2_f32_bf16.  The four lanes that share a token are summed at the end.
 template <int N, int NT>
 struct ReduceCfg {
-  static constexpr int kStageVec = N * NT * 2 * 64;            // uint4 of W per column step
+  static constexpr int kStageVec = N * NT * 2 * 64;            // u32x4 of W per column step
   static constexpr int WV = (kStageVec + 255) / 256;
   static constexpr int kLdsBytes = 2 * kStageVec * 16;
 };
@@ -234,12 +257,12 @@ template <int N, int NT>
 __global__ __launch_bounds__(256, 2) void bwd_reduce_kernel(
     const uint16_t *__restrict__ x, const uint16_t *__restrict__ y,
     const uint16_t *__restrict__ g, const uint16_t *__restrict__ gh,
-    const uint4 *__restrict__ Wp, int C, int M, int64_t T, float *__restrict__ u_raw,
+    const u32x4 *__restrict__ Wp, int C, int M, int64_t T, float *__restrict__ u_raw,
     float *__restrict__ sumsq, float *__restrict__ gH_res, float *__restrict__ gH_post,
     float *__restrict__ gH_pre) {
   using Cfg = ReduceCfg<N, NT>;
   constexpr int D = N * N + 2 * N;
-  extern __shared__ uint4 lds[];
+  extern __shared__ u32x4 lds[];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int r = lane & 15, q = lane >> 4;
   const int64_t tw = static_cast<int64_t>(blockIdx.x) * 64 + wave * 16;
@@ -252,9 +275,9 @@ __global__ __launch_bounds__(256, 2) void bwd_reduce_kernel(
   const int ncs = C / 32;
   const int sC = C / 32;   // K steps per stream
 
-  struct Tile { uint4 X[N], G[N], Y, H; };
+  struct Tile { u32x4 X[N], G[N], Y, H; };
   Tile cur, nxt;
-  uint4 wst[Cfg::WV];
+  u32x4 wst[Cfg::WV];
   f32x4 acc[NT], ss = f32x4{0.f, 0.f, 0.f, 0.f};
   float dots[D];
 #pragma unroll
@@ -265,31 +288,31 @@ __global__ __launch_bounds__(256, 2) void bwd_reduce_kernel(
   auto load_tile = [&](Tile &tl_, int cs) {
 #pragma unroll
     for (int j = 0; j < N; ++j) {
-      tl_.X[j] = *reinterpret_cast<const uint4 *>(xr + j * C + cs * 32);
-      tl_.G[j] = *reinterpret_cast<const uint4 *>(gr + j * C + cs * 32);
+      tl_.X[j] = *reinterpret_cast<const u32x4 *>(xr + j * C + cs * 32);
+      tl_.G[j] = *reinterpret_cast<const u32x4 *>(gr + j * C + cs * 32);
     }
-    tl_.Y = *reinterpret_cast<const uint4 *>(yr + cs * 32);
-    tl_.H = *reinterpret_cast<const uint4 *>(hr + cs * 32);
+    tl_.Y = *reinterpret_cast<const u32x4 *>(yr + cs * 32);
+    tl_.H = *reinterpret_cast<const u32x4 *>(hr + cs * 32);
   };
   auto load_w = [&](int cs) {
 #pragma unroll
     for (int i = 0; i < Cfg::WV; ++i) {
-      const int e = i * 256 + threadIdx.x;
-      if (e < Cfg::kStageVec) {
-        const int j = e / (NT * 128), rem = e % (NT * 128);
-        wst[i] = Wp[static_cast<size_t>(j * sC + cs) * (NT * 128) + rem];
-      }
+      int e = i * 256 + threadIdx.x;
+      if (e > Cfg::kStageVec - 1) e = Cfg::kStageVec - 1;   // surplus threads repeat the last one
+      const int j = e / (NT * 128), rem = e % (NT * 128);
+      wst[i] = Wp[static_cast<size_t>(j * sC + cs) * (NT * 128) + rem];
     }
   };
   auto store_w = [&](int buf) {
 #pragma unroll
     for (int i = 0; i < Cfg::WV; ++i) {
-      const int e = i * 256 + threadIdx.x;
-      if (e < Cfg::kStageVec) lds[buf * Cfg::kStageVec + e] = wst[i];
+      int e = i * 256 + threadIdx.x;
+      if (e > Cfg::kStageVec - 1) e = Cfg::kStageVec - 1;
+      lds[buf * Cfg::kStageVec + e] = wst[i];
     }
   };
   auto compute = [&](const Tile &tl_, int buf) {
-    const uint4 *wb = lds + buf * Cfg::kStageVec;
+    const u32x4 *wb = lds + buf * Cfg::kStageVec;
 #pragma unroll
     for (int j = 0; j < N; ++j) {
 #pragma unroll
@@ -308,17 +331,32 @@ __global__ __launch_bounds__(256, 2) void bwd_reduce_kernel(
     }
   };
 
-  load_tile(cur, 0);
+  // W before the stream tiles (see proj_mfma_kernel); the loop body is branch free
   load_w(0);
+  load_tile(cur, 0);
   store_w(0);
   __syncthreads();
-  for (int cs = 0; cs < ncs; ++cs) {
-    const bool more = cs + 1 < ncs;
-    if (more) { load_tile(nxt, cs + 1); load_w(cs + 1); }
-    compute(cur, cs & 1);
-    if (more) store_w((cs + 1) & 1);
+  int cs = 0;
+  for (; cs + 2 < ncs; cs += 2) {
+    load_w(cs + 1); load_tile(nxt, cs + 1);
+    __builtin_amdgcn_sched_barrier(0);
+    compute(cur, 0);
+    store_w(1);
     __syncthreads();
-    if (more) cur = nxt;
+    load_w(cs + 2); load_tile(cur, cs + 2);
+    __builtin_amdgcn_sched_barrier(0);
+    compute(nxt, 1);
+    store_w(0);
+    __syncthreads();
+  }
+  if (cs + 1 < ncs) {
+    load_w(cs + 1); load_tile(nxt, cs + 1);
+    compute(cur, 0);
+    store_w(1);
+    __syncthreads();
+    compute(nxt, 1);
+  } else {
+    compute(cur, 0);
   }
 
 #pragma unroll
@@ -440,70 +478,82 @@ __global__ __launch_bounds__(128) void bwd_epilogue_fast_kernel(
 template <int N>
 __global__ __launch_bounds__(256, 2) void bwd_out_kernel(
     const uint16_t *__restrict__ x, const uint16_t *__restrict__ g,
-    const uint16_t *__restrict__ gh, const uint4 *__restrict__ Wa, const float *__restrict__ cpk,
+    const uint16_t *__restrict__ gh, const u32x4 *__restrict__ Wa, const float *__restrict__ cpk,
     const uint16_t *__restrict__ vr_hi, const uint16_t *__restrict__ vr_lo, int C, int64_t T,
     int tokens_per_block, int CP, uint16_t *__restrict__ g_x, uint16_t *__restrict__ g_y) {
+  constexpr int NCP = N * N + 2 * N + 1;      // coefficients of one token
+  constexpr int NCP4 = (NCP + 3) / 4;
+  extern __shared__ u32x4 lds[];              // per wave: its N*4 W operand blocks
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int r = lane & 15, q = lane >> 4;
   const int cs = blockIdx.x * 4 + wave;            // column step of this wave
   if (cs >= C / 32) return;
   const int c0 = cs * 32 + q * 8;
   const int sC = C / 32;
-  uint4 wa[N][2][2];
+  // each lane parks its own W operands in LDS (lane-private slots, no barrier)
+  u32x4 *wl = lds + wave * (N * 4 * 64) + lane;
 #pragma unroll
   for (int j = 0; j < N; ++j)
 #pragma unroll
-    for (int h = 0; h < 2; ++h)
-#pragma unroll
-      for (int p = 0; p < 2; ++p)
-        wa[j][h][p] = Wa[(static_cast<size_t>((j * sC + cs) * 2 + h) * 2 + p) * 64 + lane];
+    for (int hp = 0; hp < 4; ++hp)
+      wl[(j * 4 + hp) * 64] = Wa[(static_cast<size_t>(j * sC + cs) * 4 + hp) * 64 + lane];
 
   const int64_t tb = static_cast<int64_t>(blockIdx.y) * tokens_per_block;
   int64_t te = tb + tokens_per_block;
   if (te > T) te = T;
-  for (int64_t t0 = tb; t0 < te; t0 += 16) {
-    const int64_t t = t0 + r;
-    const bool live = t < te;
-    const int64_t tl = live ? t : te - 1;
-    uint4 X[N], G[N], H;
+
+  struct In {
+    u32x4 X[N], G[N], H, vbh, vbl;
+    float4 cp[NCP4];
+  };
+  auto load = [&](In &in, int64_t t0) {
+    int64_t tl = t0 + r;
+    if (tl > te - 1) tl = te - 1;
 #pragma unroll
     for (int j = 0; j < N; ++j) {
-      X[j] = *reinterpret_cast<const uint4 *>(x + (tl * N + j) * C + c0);
-      G[j] = *reinterpret_cast<const uint4 *>(g + (tl * N + j) * C + c0);
+      in.X[j] = *reinterpret_cast<const u32x4 *>(x + (tl * N + j) * C + c0);
+      in.G[j] = *reinterpret_cast<const u32x4 *>(g + (tl * N + j) * C + c0);
     }
-    H = *reinterpret_cast<const uint4 *>(gh + tl * C + c0);
-    const uint4 vbh = *reinterpret_cast<const uint4 *>(vr_hi + tl * 32 + q * 8);
-    const uint4 vbl = *reinterpret_cast<const uint4 *>(vr_lo + tl * 32 + q * 8);
-    float cp[N * N + 2 * N + 1];
-    const float *cpp = cpk + tl * CP;
+    in.H = *reinterpret_cast<const u32x4 *>(gh + tl * C + c0);
+    in.vbh = *reinterpret_cast<const u32x4 *>(vr_hi + tl * 32 + q * 8);
+    in.vbl = *reinterpret_cast<const u32x4 *>(vr_lo + tl * 32 + q * 8);
+    const float4 *cpp = reinterpret_cast<const float4 *>(cpk + tl * CP);
 #pragma unroll
-    for (int e = 0; e < N * N + 2 * N + 1; ++e) cp[e] = cpp[e];
-
+    for (int e = 0; e < NCP4; ++e) in.cp[e] = cpp[e];
+  };
+  auto unpack = [](const u32x4 &v, float (&o)[8]) {
+    o[0] = bf16lo(v.x); o[1] = bf16hi(v.x); o[2] = bf16lo(v.y); o[3] = bf16hi(v.y);
+    o[4] = bf16lo(v.z); o[5] = bf16hi(v.z); o[6] = bf16lo(v.w); o[7] = bf16hi(v.w);
+  };
+  auto pack = [](const float (&o)[8]) {
+    u32x4 v;
+    v.x = cvt_pk_bf16(o[0], o[1]); v.y = cvt_pk_bf16(o[2], o[3]);
+    v.z = cvt_pk_bf16(o[4], o[5]); v.w = cvt_pk_bf16(o[6], o[7]);
+    return v;
+  };
+  auto process = [&](const In &in, int64_t t0) {
+    const int64_t t = t0 + r;
+    const bool live = t < te;
+    float cp[NCP4 * 4];
+#pragma unroll
+    for (int e = 0; e < NCP4; ++e) {
+      cp[4 * e] = in.cp[e].x; cp[4 * e + 1] = in.cp[e].y;
+      cp[4 * e + 2] = in.cp[e].z; cp[4 * e + 3] = in.cp[e].w;
+    }
     float gv[N][8], hv[8];
 #pragma unroll
-    for (int i = 0; i < N; ++i) {
-      gv[i][0] = bf16lo(G[i].x); gv[i][1] = bf16hi(G[i].x); gv[i][2] = bf16lo(G[i].y);
-      gv[i][3] = bf16hi(G[i].y); gv[i][4] = bf16lo(G[i].z); gv[i][5] = bf16hi(G[i].z);
-      gv[i][6] = bf16lo(G[i].w); gv[i][7] = bf16hi(G[i].w);
-    }
-    hv[0] = bf16lo(H.x); hv[1] = bf16hi(H.x); hv[2] = bf16lo(H.y); hv[3] = bf16hi(H.y);
-    hv[4] = bf16lo(H.z); hv[5] = bf16hi(H.z); hv[6] = bf16lo(H.w); hv[7] = bf16hi(H.w);
-
+    for (int i = 0; i < N; ++i) unpack(in.G[i], gv[i]);
+    unpack(in.H, hv);
     {   // g_y
       float o[8];
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
-        float s = 0.f;
+        float sacc = 0.f;
 #pragma unroll
-        for (int i = 0; i < N; ++i) s += cp[N * N + N + i] * gv[i][e];
-        o[e] = s;
+        for (int i = 0; i < N; ++i) sacc += cp[N * N + N + i] * gv[i][e];
+        o[e] = sacc;
       }
-      if (live) {
-        uint4 ov;
-        ov.x = cvt_pk_bf16(o[0], o[1]); ov.y = cvt_pk_bf16(o[2], o[3]);
-        ov.z = cvt_pk_bf16(o[4], o[5]); ov.w = cvt_pk_bf16(o[6], o[7]);
-        *reinterpret_cast<uint4 *>(g_y + t * C + c0) = ov;
-      }
+      if (live) *reinterpret_cast<u32x4 *>(g_y + t * C + c0) = pack(o);
     }
     const float cx = cp[N * N + 2 * N];
 #pragma unroll
@@ -511,29 +561,36 @@ __global__ __launch_bounds__(256, 2) void bwd_out_kernel(
       f32x4 wv[2];
 #pragma unroll
       for (int h = 0; h < 2; ++h) {
-        wv[h] = mfma16(wa[j][h][0], vbh, f32x4{0.f, 0.f, 0.f, 0.f});
-        wv[h] = mfma16(wa[j][h][1], vbh, wv[h]);
-        wv[h] = mfma16(wa[j][h][0], vbl, wv[h]);
+        const u32x4 wh = wl[(j * 4 + h * 2 + 0) * 64], wlo = wl[(j * 4 + h * 2 + 1) * 64];
+        wv[h] = mfma16(wh, in.vbh, f32x4{0.f, 0.f, 0.f, 0.f});
+        wv[h] = mfma16(wlo, in.vbh, wv[h]);
+        wv[h] = mfma16(wh, in.vbl, wv[h]);
       }
       float xv[8], o[8];
-      xv[0] = bf16lo(X[j].x); xv[1] = bf16hi(X[j].x); xv[2] = bf16lo(X[j].y); xv[3] = bf16hi(X[j].y);
-      xv[4] = bf16lo(X[j].z); xv[5] = bf16hi(X[j].z); xv[6] = bf16lo(X[j].w); xv[7] = bf16hi(X[j].w);
+      unpack(in.X[j], xv);
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
-        float s = wv[e >> 2][e & 3] - xv[e] * cx;
+        float sacc = wv[e >> 2][e & 3] - xv[e] * cx;
 #pragma unroll
-        for (int i = 0; i < N; ++i) s += cp[i * N + j] * gv[i][e];
-        s += cp[N * N + j] * hv[e];
-        o[e] = s;
+        for (int i = 0; i < N; ++i) sacc += cp[i * N + j] * gv[i][e];
+        sacc += cp[N * N + j] * hv[e];
+        o[e] = sacc;
       }
-      if (live) {
-        uint4 ov;
-        ov.x = cvt_pk_bf16(o[0], o[1]); ov.y = cvt_pk_bf16(o[2], o[3]);
-        ov.z = cvt_pk_bf16(o[4], o[5]); ov.w = cvt_pk_bf16(o[6], o[7]);
-        *reinterpret_cast<uint4 *>(g_x + (t * N + j) * C + c0) = ov;
-      }
+      if (live) *reinterpret_cast<u32x4 *>(g_x + (t * N + j) * C + c0) = pack(o);
     }
+  };
+
+  // software pipeline: the next 16 tokens are in flight while these are mixed
+  In cur, nxt;
+  load(cur, tb);
+  int64_t t0 = tb;
+  for (; t0 + 16 < te; t0 += 16) {
+    load(nxt, t0 + 16);
+    __builtin_amdgcn_sched_barrier(0);
+    process(cur, t0);
+    cur = nxt;
   }
+  process(cur, t0);
 }
 
 // ---------------------------------------------------------------------------
@@ -556,7 +613,7 @@ __global__ __launch_bounds__(256, 2) void bwd_gw_kernel(
   const int nsteps = K / 32;
   if (s0 >= nsteps) return;
   // selection operands: column c of half h picks row 16 h + c
-  uint4 sel[2];
+  u32x4 sel[2];
 #pragma unroll
   for (int h = 0; h < 2; ++h) {
     uint32_t w[4];
@@ -565,7 +622,7 @@ __global__ __launch_bounds__(256, 2) void bwd_gw_kernel(
       const int k0 = 8 * q + 2 * e2, k1 = k0 + 1;
       w[e2] = (k0 == 16 * h + r ? 0x3F80u : 0u) | (k1 == 16 * h + r ? 0x3F800000u : 0u);
     }
-    sel[h] = uint4{w[0], w[1], w[2], w[3]};
+    sel[h] = u32x4{w[0], w[1], w[2], w[3]};
   }
   f32x4 acc[CSW][2][NT];
 #pragma unroll
@@ -578,8 +635,13 @@ __global__ __launch_bounds__(256, 2) void bwd_gw_kernel(
   const int64_t b0 = static_cast<int64_t>(blockIdx.y) * blks_per_chunk;
   int64_t b1 = b0 + blks_per_chunk;
   if (b1 > nblk) b1 = nblk;
-  for (int64_t blk = b0; blk < b1; ++blk) {
-    uint4 X[CSW][2];
+  if (b0 >= b1) return;
+
+  struct In {
+    u32x4 X[CSW][2];
+    u32x2 v[NT][4];   // hi: tokens 4q.., 16+4q.. ; lo: the same
+  };
+  auto load = [&](In &in, int64_t blk) {
 #pragma unroll
     for (int gI = 0; gI < 2; ++gI) {
       int64_t t = blk * 32 + gI * 16 + r;
@@ -587,38 +649,50 @@ __global__ __launch_bounds__(256, 2) void bwd_gw_kernel(
 #pragma unroll
       for (int c = 0; c < CSW; ++c) {
         const int s = s0 + c < nsteps ? s0 + c : nsteps - 1;
-        X[c][gI] = *reinterpret_cast<const uint4 *>(x + t * K + s * 32 + q * 8);
+        in.X[c][gI] = *reinterpret_cast<const u32x4 *>(x + t * K + s * 32 + q * 8);
       }
     }
-    uint4 va[NT][2];
 #pragma unroll
     for (int mt = 0; mt < NT; ++mt) {
       const size_t row = (static_cast<size_t>(blk) * MP16 + mt * 16 + r) * 32;
-      const uint2 h0 = *reinterpret_cast<const uint2 *>(vrT_hi + row + 4 * q);
-      const uint2 h1 = *reinterpret_cast<const uint2 *>(vrT_hi + row + 16 + 4 * q);
-      const uint2 l0 = *reinterpret_cast<const uint2 *>(vrT_lo + row + 4 * q);
-      const uint2 l1 = *reinterpret_cast<const uint2 *>(vrT_lo + row + 16 + 4 * q);
-      va[mt][0] = uint4{h0.x, h0.y, h1.x, h1.y};
-      va[mt][1] = uint4{l0.x, l0.y, l1.x, l1.y};
+      in.v[mt][0] = *reinterpret_cast<const u32x2 *>(vrT_hi + row + 4 * q);
+      in.v[mt][1] = *reinterpret_cast<const u32x2 *>(vrT_hi + row + 16 + 4 * q);
+      in.v[mt][2] = *reinterpret_cast<const u32x2 *>(vrT_lo + row + 4 * q);
+      in.v[mt][3] = *reinterpret_cast<const u32x2 *>(vrT_lo + row + 16 + 4 * q);
     }
+  };
+  auto process = [&](const In &in) {
 #pragma unroll
     for (int c = 0; c < CSW; ++c) {
 #pragma unroll
       for (int h = 0; h < 2; ++h) {
         const f32x4 z = f32x4{0.f, 0.f, 0.f, 0.f};
-        const f32x4 t0 = mfma16(X[c][0], sel[h], z);   // tokens 4q+i of the first 16
-        const f32x4 t1 = mfma16(X[c][1], sel[h], z);   // tokens 4q+i of the second 16
-        uint4 bt;
+        const f32x4 t0 = mfma16(in.X[c][0], sel[h], z);   // tokens 4q+i of the first 16
+        const f32x4 t1 = mfma16(in.X[c][1], sel[h], z);   // tokens 4q+i of the second 16
+        u32x4 bt;
         bt.x = cvt_pk_bf16(t0[0], t0[1]); bt.y = cvt_pk_bf16(t0[2], t0[3]);
         bt.z = cvt_pk_bf16(t1[0], t1[1]); bt.w = cvt_pk_bf16(t1[2], t1[3]);
 #pragma unroll
         for (int mt = 0; mt < NT; ++mt) {
-          acc[c][h][mt] = mfma16(va[mt][0], bt, acc[c][h][mt]);
-          acc[c][h][mt] = mfma16(va[mt][1], bt, acc[c][h][mt]);
+          const u32x4 vh = u32x4{in.v[mt][0].x, in.v[mt][0].y, in.v[mt][1].x, in.v[mt][1].y};
+          const u32x4 vl = u32x4{in.v[mt][2].x, in.v[mt][2].y, in.v[mt][3].x, in.v[mt][3].y};
+          acc[c][h][mt] = mfma16(vh, bt, acc[c][h][mt]);
+          acc[c][h][mt] = mfma16(vl, bt, acc[c][h][mt]);
         }
       }
     }
+  };
+  In cur, nxt;
+  load(cur, b0);
+  int64_t blk = b0;
+  for (; blk + 1 < b1; ++blk) {
+    load(nxt, blk + 1);
+    __builtin_amdgcn_sched_barrier(0);
+    process(cur);
+    cur = nxt;
   }
+  process(cur);
+
   float *dst = out + static_cast<size_t>(blockIdx.y) * K * M;
 #pragma unroll
   for (int c = 0; c < CSW; ++c) {
@@ -680,7 +754,7 @@ hipError_t launch_proj_mfma(const mhcl_desc &d, int M, const void *x, const void
       if (e != hipSuccess) return e;
     }
     hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>((d.T + 127) / 128)), dim3(256), lds, s,
-                       static_cast<const uint16_t *>(x), static_cast<const uint4 *>(Wp), K, M, d.T,
+                       static_cast<const uint16_t *>(x), static_cast<const u32x4 *>(Wp), K, M, d.T,
                        u_raw, sumsq);
     return hipGetLastError();
   });
@@ -744,7 +818,7 @@ hipError_t launch_bwd_reduce(const mhcl_desc &d, int M, const void *x, const voi
     hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>((d.T + 63) / 64)), dim3(256),
                        (ReduceCfg<N, NT>::kLdsBytes), s, static_cast<const uint16_t *>(x),
                        static_cast<const uint16_t *>(y), static_cast<const uint16_t *>(g_xout),
-                       static_cast<const uint16_t *>(g_h), reinterpret_cast<const uint4 *>(w.Wp),
+                       static_cast<const uint16_t *>(g_h), reinterpret_cast<const u32x4 *>(w.Wp),
                        d.C, M, d.T, w.u_raw, w.sumsq, w.gH_res, w.gH_post, w.gH_pre);
     return hipGetLastError();
   };
@@ -792,9 +866,10 @@ hipError_t launch_bwd_out(const mhcl_desc &d, const void *x, const void *g_xout,
   auto go = [&](auto nn) {
     constexpr int N = decltype(nn)::value;
     const dim3 grid((d.C / 32 + 3) / 4, static_cast<unsigned>((d.T + kTokensPerBlock - 1) / kTokensPerBlock));
-    hipLaunchKernelGGL(bwd_out_kernel<N>, grid, dim3(256), 0, s, static_cast<const uint16_t *>(x),
+    hipLaunchKernelGGL(bwd_out_kernel<N>, grid, dim3(256), 4 * N * 4 * 64 * 16, s,
+                       static_cast<const uint16_t *>(x),
                        static_cast<const uint16_t *>(g_xout), static_cast<const uint16_t *>(g_h),
-                       reinterpret_cast<const uint4 *>(w.Wa), w.cpk, w.vr_hi, w.vr_lo, d.C, d.T,
+                       reinterpret_cast<const u32x4 *>(w.Wa), w.cpk, w.vr_hi, w.vr_lo, d.C, d.T,
                        kTokensPerBlock, w.CP, static_cast<uint16_t *>(g_x),
                        static_cast<uint16_t *>(g_y));
     return hipGetLastError();
