@@ -49,7 +49,7 @@ struct CoeffsWs {
 };
 
 struct BwdWs {
-  float *u_raw, *sumsq, *gH_res, *gH_pre, *gH_post, *partials;
+  float *u_raw, *sumsq, *gH_res, *gH_pre, *gH_post, *partials, *psum;
   char *Wp;
   BwdTokenBufs tok;
   size_t bytes;
@@ -74,6 +74,7 @@ struct BwdWs {
     const int chunks = gw_chunks_generic(d);
     partials = chunks > 1 ? c.take<float>(static_cast<size_t>(chunks) * n * d.C * M) : nullptr;
     Wp = fast_path_ok(d) ? c.take<char>(packed_w_b_bytes(d, M)) : nullptr;
+    psum = c.take<float>(static_cast<size_t>(param_sum_blocks(d)) * (M + 3));
     bytes = c.off;
   }
 };
@@ -301,7 +302,7 @@ int mhcl_coeffs_bwd(const mhcl_desc *desc, const void *x, const float *W, const 
                                       g_H_post, w.tok, s));
   MHCL_HIP(launch_gx_generic(*desc, M, false, x, W, nullptr, nullptr, w.tok, g_x, nullptr, s));
   MHCL_HIP(launch_gw_generic(*desc, M, x, w.tok.vr, w.partials, g_W, s));
-  MHCL_HIP(launch_param_sums(*desc, M, w.tok.gz, g_b, g_alpha, s));
+  MHCL_HIP(launch_param_sums(*desc, M, w.tok.gz, g_b, g_alpha, w.psum, s));
   return MHCL_OK;
 }
 
@@ -346,7 +347,7 @@ int mhcl_bwd_fused(const mhcl_desc *desc, const void *x, const void *y, const fl
       StageBracket br(MHCL_STAGE_BWD_GW, s);
       MHCL_HIP(launch_bwd_gw(*desc, M, x, f, g_W, s));
     }
-    MHCL_HIP(launch_param_sums(*desc, M, f.gz, g_b, g_alpha, s));
+    MHCL_HIP(launch_param_sums(*desc, M, f.gz, g_b, g_alpha, f.psum, s));
     return MHCL_OK;
   }
   BwdWs w(*desc, ws, true);
@@ -359,7 +360,7 @@ int mhcl_bwd_fused(const mhcl_desc *desc, const void *x, const void *y, const fl
     MHCL_HIP(launch_gx_generic(*desc, M, true, x, W, g_xout, g_h, w.tok, g_x, g_y, s));
   }
   MHCL_HIP(launch_gw_generic(*desc, M, x, w.tok.vr, w.partials, g_W, s));
-  MHCL_HIP(launch_param_sums(*desc, M, w.tok.gz, g_b, g_alpha, s));
+  MHCL_HIP(launch_param_sums(*desc, M, w.tok.gz, g_b, g_alpha, w.psum, s));
   return MHCL_OK;
 }
 

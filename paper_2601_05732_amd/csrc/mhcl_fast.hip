@@ -48,12 +48,13 @@ __global__ __launch_bounds__(256) void pack_w_b_kernel(const float *__restrict__
 // Block = 4 waves, each wave owns 32 tokens (two 16-token A tiles) and walks
 // the whole K = nC range; the block's waves share each chunk of packed W
 // through LDS (double buffered).  A tiles come straight from HBM in MFMA lane
-// order: lane (r, q) reads 16 bytes of token r at column 32 s + 8 q.
+// order: lane (r, q) reads 16 bytes of token r at column 32 s + 8 q, several
+// consecutive steps s back to back.
 // sum(x^2) is the diagonal of the tile's Gram matrix A A^T, one more MFMA with
 // the A tile as both operands.
 template <int NT>
 struct ProjCfg {
-  static constexpr int KC = NT <= 2 ? 8 : (NT == 3 ? 4 : 2);   // K steps per chunk
+  static constexpr int KC = NT == 2 ? 8 : (NT == 9 ? 2 : 4);   // K steps per chunk
   static constexpr int kChunkVec = KC * NT * 2 * 64;           // u32x4 per chunk
   static constexpr int kLdsBytes = 2 * kChunkVec * 16;
 };
@@ -101,7 +102,8 @@ __global__ __launch_bounds__(256, 2) void proj_mfma_kernel(const uint16_t *__res
       const int step = c * KC + s;
       const int sc = step < nsteps ? step : nsteps - 1;
 #pragma unroll
-      for (int g = 0; g < TG; ++g) dst[g][s] = *reinterpret_cast<const u32x4 *>(row[g] + sc * 32);
+      for (int g = 0; g < TG; ++g)
+        dst[g][s] = *reinterpret_cast<const u32x4 *>(row[g] + sc * 32);
     }
   };
   auto load_w = [&](int c) {
@@ -199,11 +201,11 @@ __global__ __launch_bounds__(256, 2) void proj_mfma_kernel(const uint16_t *__res
 __global__ __launch_bounds__(256) void pack_w_a_kernel(const float *__restrict__ W, int K, int M,
                                                        int MS, uint4 *__restrict__ Wa) {
   const int idx = blockIdx.x * 256 + threadIdx.x;
-  const int lane = idx & 63, blk = idx >> 6;   // blk = (s*2 + h)*MS + ms
-  if (blk >= (K / 32) * 2 * MS) return;
-  const int ms = blk % MS, h = (blk / MS) & 1, s = blk / (2 * MS);
+  const int lane = idx & 63, blk = idx >> 6;   // blk = (S*4 + h)*MS + ms
+  if (blk >= (K / 64) * 4 * MS) return;
+  const int ms = blk % MS, h = (blk / MS) & 3, S = blk / (4 * MS);
   const int r = lane & 15, q = lane >> 4;
-  const int k = 32 * s + 8 * (r >> 2) + 4 * h + (r & 3);
+  const int k = 64 * S + 32 * (h >> 1) + 8 * (r >> 2) + 4 * (h & 1) + (r & 3);
   uint16_t hi[8], lo[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
@@ -220,7 +222,6 @@ __global__ __launch_bounds__(256) void pack_w_a_kernel(const float *__restrict__
   Wa[(static_cast<size_t>(blk) * 2 + 1) * 64 + lane] = vl;
 }
 
-// sum over 8 bf16 pairs-of-products: acc + <a, b>, products exact, fp32 sums
 __device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float acc) {
   return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a), __builtin_bit_cast(bf16x2, b),
                                          acc, false);
@@ -241,14 +242,15 @@ __device__ __forceinline__ float dot8_bf16(const u32x4 &a, const u32x4 &b, float
 //   u_raw, sumsq                      (recomputed projection, as in forward)
 //   g_H_res[i][j] = <g_xout[i], x[j]>, g_H_post[i] = <g_xout[i], y>,
 //   g_H_pre[j]    = <g_h, x[j]>       (reductions over C)
-// Block = 4 waves x 16 tokens.  The loop runs over 32-column steps of C; at
-// each step a lane holds, for its token, 8 columns of all n streams of x and
+// Block = 4 waves x 16 tokens.  The loop runs over 64-column steps of C; at
+// each step a lane holds, for its token, 2 x 8 columns (two loads issued back
+// to back, so that four lanes consume a whole 128-byte line per visit) of all n streams of x and
 // g_xout and of y and g_h, feeds the x tiles to the MFMA projection (W blocks
 // of that step staged in LDS, double buffered) and the dot products to
 // v_dot2_f32_bf16.  The four lanes that share a token are summed at the end.
 template <int N, int NT>
 struct ReduceCfg {
-  static constexpr int kStageVec = N * NT * 2 * 64;            // u32x4 of W per column step
+  static constexpr int kStageVec = N * 2 * NT * 2 * 64;        // 16-byte words of W per step
   static constexpr int WV = (kStageVec + 255) / 256;
   static constexpr int kLdsBytes = 2 * kStageVec * 16;
 };
@@ -272,11 +274,10 @@ __global__ __launch_bounds__(256, 2) void bwd_reduce_kernel(
   const uint16_t *gr = g + tl * N * C + q * 8;
   const uint16_t *yr = y + tl * C + q * 8;
   const uint16_t *hr = gh + tl * C + q * 8;
-  const int ncs = C / 32;
-  const int sC = C / 32;   // K steps per stream
+  const int ncs = C / 64;   // 64-column steps; also per-stream stride of W in such steps
 
-  struct Tile { u32x4 X[N], G[N], Y, H; };
-  Tile cur, nxt;
+  struct Tile { u32x4 X[N][2], G[N][2], Y[2], H[2]; };
+  Tile tile;
   u32x4 wst[Cfg::WV];
   f32x4 acc[NT], ss = f32x4{0.f, 0.f, 0.f, 0.f};
   float dots[D];
@@ -285,22 +286,28 @@ __global__ __launch_bounds__(256, 2) void bwd_reduce_kernel(
 #pragma unroll
   for (int e = 0; e < D; ++e) dots[e] = 0.f;
 
-  auto load_tile = [&](Tile &tl_, int cs) {
+  auto load_tile = [&](int cs) {
 #pragma unroll
-    for (int j = 0; j < N; ++j) {
-      tl_.X[j] = *reinterpret_cast<const u32x4 *>(xr + j * C + cs * 32);
-      tl_.G[j] = *reinterpret_cast<const u32x4 *>(gr + j * C + cs * 32);
+    for (int j = 0; j < N; ++j)
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        tile.X[j][u] = *reinterpret_cast<const u32x4 *>(xr + j * C + cs * 64 + u * 32);
+        tile.G[j][u] = *reinterpret_cast<const u32x4 *>(gr + j * C + cs * 64 + u * 32);
+      }
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      tile.Y[u] = *reinterpret_cast<const u32x4 *>(yr + cs * 64 + u * 32);
+      tile.H[u] = *reinterpret_cast<const u32x4 *>(hr + cs * 64 + u * 32);
     }
-    tl_.Y = *reinterpret_cast<const u32x4 *>(yr + cs * 32);
-    tl_.H = *reinterpret_cast<const u32x4 *>(hr + cs * 32);
   };
+  // W blocks of step cs: for stream j the 2 K steps 2 (j ncs + cs) + u, NT tiles, hi/lo
   auto load_w = [&](int cs) {
 #pragma unroll
     for (int i = 0; i < Cfg::WV; ++i) {
       int e = i * 256 + threadIdx.x;
       if (e > Cfg::kStageVec - 1) e = Cfg::kStageVec - 1;   // surplus threads repeat the last one
-      const int j = e / (NT * 128), rem = e % (NT * 128);
-      wst[i] = Wp[static_cast<size_t>(j * sC + cs) * (NT * 128) + rem];
+      const int j = e / (NT * 256), rem = e % (NT * 256);
+      wst[i] = Wp[static_cast<size_t>(j * ncs + cs) * (NT * 256) + rem];
     }
   };
   auto store_w = [&](int buf) {
@@ -311,52 +318,50 @@ __global__ __launch_bounds__(256, 2) void bwd_reduce_kernel(
       lds[buf * Cfg::kStageVec + e] = wst[i];
     }
   };
-  auto compute = [&](const Tile &tl_, int buf) {
+  auto compute = [&](int buf) {
     const u32x4 *wb = lds + buf * Cfg::kStageVec;
 #pragma unroll
     for (int j = 0; j < N; ++j) {
 #pragma unroll
-      for (int jt = 0; jt < NT; ++jt) {
-        acc[jt] = mfma16(tl_.X[j], wb[((j * NT + jt) * 2 + 0) * 64 + lane], acc[jt]);
-        acc[jt] = mfma16(tl_.X[j], wb[((j * NT + jt) * 2 + 1) * 64 + lane], acc[jt]);
+      for (int u = 0; u < 2; ++u) {
+#pragma unroll
+        for (int jt = 0; jt < NT; ++jt) {
+          acc[jt] = mfma16(tile.X[j][u], wb[(((j * 2 + u) * NT + jt) * 2 + 0) * 64 + lane], acc[jt]);
+          acc[jt] = mfma16(tile.X[j][u], wb[(((j * 2 + u) * NT + jt) * 2 + 1) * 64 + lane], acc[jt]);
+        }
+        ss = mfma16(tile.X[j][u], tile.X[j][u], ss);
       }
-      ss = mfma16(tl_.X[j], tl_.X[j], ss);
-    }
 #pragma unroll
-    for (int i = 0; i < N; ++i) {
+      for (int u = 0; u < 2; ++u) {
 #pragma unroll
-      for (int j = 0; j < N; ++j) dots[i * N + j] = dot8_bf16(tl_.G[i], tl_.X[j], dots[i * N + j]);
-      dots[N * N + i] = dot8_bf16(tl_.G[i], tl_.Y, dots[N * N + i]);
-      dots[N * N + N + i] = dot8_bf16(tl_.H, tl_.X[i], dots[N * N + N + i]);
+        for (int i = 0; i < N; ++i)
+          dots[i * N + j] = dot8_bf16(tile.G[i][u], tile.X[j][u], dots[i * N + j]);
+        dots[N * N + j] = dot8_bf16(tile.G[j][u], tile.Y[u], dots[N * N + j]);
+        dots[N * N + N + j] = dot8_bf16(tile.H[u], tile.X[j][u], dots[N * N + N + j]);
+      }
+      // keeps the W operands of one stream at a time in registers
+      __builtin_amdgcn_sched_barrier(0);
     }
   };
 
-  // W before the stream tiles (see proj_mfma_kernel); the loop body is branch free
+  // One tile at a time per wave; the block's second resident copy and the other
+  // waves keep HBM busy while this wave computes.  Per step: request W of the
+  // next step, then this step's stream tile; park W in the idle LDS buffer as
+  // soon as it is there (loads return in order, the tile stays in flight);
+  // then compute on the tile.  The barrier both publishes the new W buffer and
+  // frees the one just read.
   load_w(0);
-  load_tile(cur, 0);
   store_w(0);
   __syncthreads();
-  int cs = 0;
-  for (; cs + 2 < ncs; cs += 2) {
-    load_w(cs + 1); load_tile(nxt, cs + 1);
+  for (int cs = 0; cs < ncs; ++cs) {
+    const int nx = cs + 1 < ncs ? cs + 1 : cs;   // last step re-stages itself (unused)
+    load_w(nx);
+    load_tile(cs);
     __builtin_amdgcn_sched_barrier(0);
-    compute(cur, 0);
-    store_w(1);
-    __syncthreads();
-    load_w(cs + 2); load_tile(cur, cs + 2);
+    store_w((cs + 1) & 1);
     __builtin_amdgcn_sched_barrier(0);
-    compute(nxt, 1);
-    store_w(0);
+    compute(cs & 1);
     __syncthreads();
-  }
-  if (cs + 1 < ncs) {
-    load_w(cs + 1); load_tile(nxt, cs + 1);
-    compute(cur, 0);
-    store_w(1);
-    __syncthreads();
-    compute(nxt, 1);
-  } else {
-    compute(cur, 0);
   }
 
 #pragma unroll
@@ -470,11 +475,13 @@ __global__ __launch_bounds__(128) void bwd_epilogue_fast_kernel(
 // Backward pass 2a: the stream outputs.
 //   g_x[j] = sum_i H_res[i][j] g_xout[i] + H_pre[j] g_h + (W vr)[j] - x[j] coefx
 //   g_y    = sum_i H_post[i] g_xout[i]
-// summed in fp32 and rounded to bf16 once.  A wave owns one 32-column step of C
-// (all n streams) and walks a chunk of tokens 16 at a time; its slice of W (A
-// layout, hi + lo) stays in registers for the whole walk.  (W vr) comes out of
-// the MFMA already in the lane order of the stream loads: lane (token, q) gets
-// the 8 columns it also loaded.
+// summed in fp32 and rounded to bf16 once.  A block owns one 64-column step of C
+// (all n streams) and a chunk of tokens; its slice of W (A layout, hi + lo)
+// sits in LDS for the whole walk and its waves take the chunk's 16-token
+// groups in turn.  A lane owns 2 x 8 columns of its token (columns 32 u + 8 q
+// + 0..7, u = 0, 1: four lanes read and write whole 128-byte lines in two back
+// to back accesses).  (W vr) comes out of the MFMAs already in that ownership:
+// lane (token, q), quarter h = 2 u + hh gets rows 32 u + 8 q + 4 hh + 0..3.
 template <int N>
 __global__ __launch_bounds__(256, 2) void bwd_out_kernel(
     const uint16_t *__restrict__ x, const uint16_t *__restrict__ g,
@@ -483,44 +490,24 @@ __global__ __launch_bounds__(256, 2) void bwd_out_kernel(
     int tokens_per_block, int CP, uint16_t *__restrict__ g_x, uint16_t *__restrict__ g_y) {
   constexpr int NCP = N * N + 2 * N + 1;      // coefficients of one token
   constexpr int NCP4 = (NCP + 3) / 4;
-  extern __shared__ u32x4 lds[];              // per wave: its N*4 W operand blocks
+  constexpr int kSliceVec = N * 4 * 2 * 64;   // 16-byte words of W per 64-column step
+  extern __shared__ u32x4 lds[];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int r = lane & 15, q = lane >> 4;
-  const int cs = blockIdx.x * 4 + wave;            // column step of this wave
-  if (cs >= C / 32) return;
-  const int c0 = cs * 32 + q * 8;
-  const int sC = C / 32;
-  // each lane parks its own W operands in LDS (lane-private slots, no barrier)
-  u32x4 *wl = lds + wave * (N * 4 * 64) + lane;
-#pragma unroll
-  for (int j = 0; j < N; ++j)
-#pragma unroll
-    for (int hp = 0; hp < 4; ++hp)
-      wl[(j * 4 + hp) * 64] = Wa[(static_cast<size_t>(j * sC + cs) * 4 + hp) * 64 + lane];
+  const int S = blockIdx.x;                    // 64-column step of this block
+  const int c0 = S * 64 + q * 8;
+  const int nS = C / 64;
+  for (int e = threadIdx.x; e < kSliceVec; e += 256) {
+    const int j = e / 512, rem = e % 512;      // 512 words per (stream, step): 4 quarters x hi/lo
+    lds[e] = Wa[static_cast<size_t>(j * nS + S) * 512 + rem];
+  }
+  __syncthreads();
+  const u32x4 *wl = lds + lane;
 
   const int64_t tb = static_cast<int64_t>(blockIdx.y) * tokens_per_block;
   int64_t te = tb + tokens_per_block;
   if (te > T) te = T;
 
-  struct In {
-    u32x4 X[N], G[N], H, vbh, vbl;
-    float4 cp[NCP4];
-  };
-  auto load = [&](In &in, int64_t t0) {
-    int64_t tl = t0 + r;
-    if (tl > te - 1) tl = te - 1;
-#pragma unroll
-    for (int j = 0; j < N; ++j) {
-      in.X[j] = *reinterpret_cast<const u32x4 *>(x + (tl * N + j) * C + c0);
-      in.G[j] = *reinterpret_cast<const u32x4 *>(g + (tl * N + j) * C + c0);
-    }
-    in.H = *reinterpret_cast<const u32x4 *>(gh + tl * C + c0);
-    in.vbh = *reinterpret_cast<const u32x4 *>(vr_hi + tl * 32 + q * 8);
-    in.vbl = *reinterpret_cast<const u32x4 *>(vr_lo + tl * 32 + q * 8);
-    const float4 *cpp = reinterpret_cast<const float4 *>(cpk + tl * CP);
-#pragma unroll
-    for (int e = 0; e < NCP4; ++e) in.cp[e] = cpp[e];
-  };
   auto unpack = [](const u32x4 &v, float (&o)[8]) {
     o[0] = bf16lo(v.x); o[1] = bf16hi(v.x); o[2] = bf16lo(v.y); o[3] = bf16hi(v.y);
     o[4] = bf16lo(v.z); o[5] = bf16hi(v.z); o[6] = bf16lo(v.w); o[7] = bf16hi(v.w);
@@ -531,6 +518,30 @@ __global__ __launch_bounds__(256, 2) void bwd_out_kernel(
     v.z = cvt_pk_bf16(o[4], o[5]); v.w = cvt_pk_bf16(o[6], o[7]);
     return v;
   };
+
+  struct In {
+    u32x4 X[N][2], G[N][2], H[2], vbh, vbl;
+    float4 cp[NCP4];
+  };
+  auto load = [&](In &in, int64_t t0) {
+    int64_t tl = t0 + r;
+    if (tl > te - 1) tl = te - 1;
+#pragma unroll
+    for (int j = 0; j < N; ++j)
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        in.X[j][u] = *reinterpret_cast<const u32x4 *>(x + (tl * N + j) * C + c0 + u * 32);
+        in.G[j][u] = *reinterpret_cast<const u32x4 *>(g + (tl * N + j) * C + c0 + u * 32);
+      }
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+      in.H[u] = *reinterpret_cast<const u32x4 *>(gh + tl * C + c0 + u * 32);
+    in.vbh = *reinterpret_cast<const u32x4 *>(vr_hi + tl * 32 + q * 8);
+    in.vbl = *reinterpret_cast<const u32x4 *>(vr_lo + tl * 32 + q * 8);
+    const float4 *cpp = reinterpret_cast<const float4 *>(cpk + tl * CP);
+#pragma unroll
+    for (int e = 0; e < NCP4; ++e) in.cp[e] = cpp[e];
+  };
   auto process = [&](const In &in, int64_t t0) {
     const int64_t t = t0 + r;
     const bool live = t < te;
@@ -540,57 +551,76 @@ __global__ __launch_bounds__(256, 2) void bwd_out_kernel(
       cp[4 * e] = in.cp[e].x; cp[4 * e + 1] = in.cp[e].y;
       cp[4 * e + 2] = in.cp[e].z; cp[4 * e + 3] = in.cp[e].w;
     }
-    float gv[N][8], hv[8];
-#pragma unroll
-    for (int i = 0; i < N; ++i) unpack(in.G[i], gv[i]);
-    unpack(in.H, hv);
-    {   // g_y
-      float o[8];
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        float sacc = 0.f;
-#pragma unroll
-        for (int i = 0; i < N; ++i) sacc += cp[N * N + N + i] * gv[i][e];
-        o[e] = sacc;
-      }
-      if (live) *reinterpret_cast<u32x4 *>(g_y + t * C + c0) = pack(o);
-    }
     const float cx = cp[N * N + 2 * N];
+    // both 8-column halves of a row are produced first and stored back to back,
+    // so that every visit writes whole 128-byte lines
+    float gv[2][N][8], hv[2][8];
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+#pragma unroll
+      for (int i = 0; i < N; ++i) unpack(in.G[i][u], gv[u][i]);
+      unpack(in.H[u], hv[u]);
+    }
+    {   // g_y
+      u32x4 ov[2];
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        float o[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          float sacc = 0.f;
+#pragma unroll
+          for (int i = 0; i < N; ++i) sacc += cp[N * N + N + i] * gv[u][i][e];
+          o[e] = sacc;
+        }
+        ov[u] = pack(o);
+      }
+      if (live) {
+        *reinterpret_cast<u32x4 *>(g_y + t * C + c0) = ov[0];
+        *reinterpret_cast<u32x4 *>(g_y + t * C + c0 + 32) = ov[1];
+      }
+    }
 #pragma unroll
     for (int j = 0; j < N; ++j) {
-      f32x4 wv[2];
+      u32x4 ov[2];
 #pragma unroll
-      for (int h = 0; h < 2; ++h) {
-        const u32x4 wh = wl[(j * 4 + h * 2 + 0) * 64], wlo = wl[(j * 4 + h * 2 + 1) * 64];
-        wv[h] = mfma16(wh, in.vbh, f32x4{0.f, 0.f, 0.f, 0.f});
-        wv[h] = mfma16(wlo, in.vbh, wv[h]);
-        wv[h] = mfma16(wh, in.vbl, wv[h]);
+      for (int u = 0; u < 2; ++u) {
+        f32x4 wv[2];
+#pragma unroll
+        for (int hh = 0; hh < 2; ++hh) {
+          const int h = 2 * u + hh;
+          const u32x4 wh = wl[((j * 4 + h) * 2 + 0) * 64], wlo = wl[((j * 4 + h) * 2 + 1) * 64];
+          wv[hh] = mfma16(wh, in.vbh, f32x4{0.f, 0.f, 0.f, 0.f});
+          wv[hh] = mfma16(wlo, in.vbh, wv[hh]);
+          wv[hh] = mfma16(wh, in.vbl, wv[hh]);
+        }
+        float xv[8], o[8];
+        unpack(in.X[j][u], xv);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          float sacc = wv[e >> 2][e & 3] - xv[e] * cx;
+#pragma unroll
+          for (int i = 0; i < N; ++i) sacc += cp[i * N + j] * gv[u][i][e];
+          sacc += cp[N * N + j] * hv[u][e];
+          o[e] = sacc;
+        }
+        ov[u] = pack(o);
       }
-      float xv[8], o[8];
-      unpack(in.X[j], xv);
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        float sacc = wv[e >> 2][e & 3] - xv[e] * cx;
-#pragma unroll
-        for (int i = 0; i < N; ++i) sacc += cp[i * N + j] * gv[i][e];
-        sacc += cp[N * N + j] * hv[e];
-        o[e] = sacc;
+      if (live) {
+        *reinterpret_cast<u32x4 *>(g_x + (t * N + j) * C + c0) = ov[0];
+        *reinterpret_cast<u32x4 *>(g_x + (t * N + j) * C + c0 + 32) = ov[1];
       }
-      if (live) *reinterpret_cast<u32x4 *>(g_x + (t * N + j) * C + c0) = pack(o);
+      __builtin_amdgcn_sched_barrier(0);   // one stream's operands and results at a time
     }
   };
 
-  // software pipeline: the next 16 tokens are in flight while these are mixed
-  In cur, nxt;
-  load(cur, tb);
-  int64_t t0 = tb;
-  for (; t0 + 16 < te; t0 += 16) {
-    load(nxt, t0 + 16);
+  // One 16-token group at a time per wave; the other resident waves keep HBM busy.
+  In in;
+  for (int64_t t0 = tb + wave * 16; t0 < te; t0 += 64) {
+    load(in, t0);
     __builtin_amdgcn_sched_barrier(0);
-    process(cur, t0);
-    cur = nxt;
+    process(in, t0);
   }
-  process(cur, t0);
 }
 
 // ---------------------------------------------------------------------------
@@ -798,12 +828,13 @@ FastBwdWs::FastBwdWs(const mhcl_desc &d, void *ws) {
   Wp = c.take<char>(packed_b_bytes(K, M));
   Wa = c.take<char>(packed_a_bytes(K, M));
   partials = c.take<float>(static_cast<size_t>(gw_chunks_fast(d)) * K * M);
+  psum = c.take<float>(static_cast<size_t>(param_sum_blocks(d)) * (M + 3));
   bytes = c.off;
 }
 
 hipError_t launch_pack_w_a(const mhcl_desc &d, int M, const float *W, void *Wa, hipStream_t s) {
   const int K = d.n * d.C, MS = logit_steps(M);
-  const int threads = (K / 32) * 2 * MS * 64;
+  const int threads = (K / 64) * 4 * MS * 64;
   hipLaunchKernelGGL(pack_w_a_kernel, dim3((threads + 255) / 256), dim3(256), 0, s, W, K, M, MS,
                      static_cast<uint4 *>(Wa));
   return hipGetLastError();
@@ -865,8 +896,8 @@ hipError_t launch_bwd_out(const mhcl_desc &d, const void *x, const void *g_xout,
   constexpr int kTokensPerBlock = 512;
   auto go = [&](auto nn) {
     constexpr int N = decltype(nn)::value;
-    const dim3 grid((d.C / 32 + 3) / 4, static_cast<unsigned>((d.T + kTokensPerBlock - 1) / kTokensPerBlock));
-    hipLaunchKernelGGL(bwd_out_kernel<N>, grid, dim3(256), 4 * N * 4 * 64 * 16, s,
+    const dim3 grid(d.C / 64, static_cast<unsigned>((d.T + kTokensPerBlock - 1) / kTokensPerBlock));
+    hipLaunchKernelGGL(bwd_out_kernel<N>, grid, dim3(256), N * 4 * 2 * 64 * 16, s,
                        static_cast<const uint16_t *>(x),
                        static_cast<const uint16_t *>(g_xout), static_cast<const uint16_t *>(g_h),
                        reinterpret_cast<const u32x4 *>(w.Wa), w.cpk, w.vr_hi, w.vr_lo, d.C, d.T,

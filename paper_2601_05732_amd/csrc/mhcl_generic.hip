@@ -469,24 +469,41 @@ __global__ __launch_bounds__(kBlock) void sum_partials_kernel(const float *__res
   out[i] = s;
 }
 
-// Column sums of a [T, ld] matrix, one block per column, fixed order.
-// Column c goes to dstA[c] if c < nA, else to dstB[c - nA].
-__global__ __launch_bounds__(kBlock) void colsum_kernel(const float *__restrict__ src, int64_t T,
-                                                        int ld, int nA, float *__restrict__ dstA,
-                                                        float *__restrict__ dstB) {
-  __shared__ float red[kBlock];
-  const int c = blockIdx.x;
-  float s = 0.f;
-  for (int64_t t = threadIdx.x; t < T; t += kBlock) s += src[t * ld + c];
-  red[threadIdx.x] = s;
-  __syncthreads();
-  for (int w = kBlock / 2; w > 0; w >>= 1) {
-    if (threadIdx.x < w) red[threadIdx.x] += red[threadIdx.x + w];
+// Column sums of a [T, ld] matrix in two fixed-order stages.  Stage 1: block b
+// sums rows [b*rows_per_block, ...) of every column (4 row lanes x 64 column
+// lanes) into part[b][ld].  Stage 2: one block adds the partials in block order;
+// column c goes to dstA[c] if c < nA, else to dstB[c - nA].
+__global__ __launch_bounds__(kBlock) void colsum_stage1_kernel(const float *__restrict__ src,
+                                                               int64_t T, int ld,
+                                                               int64_t rows_per_block,
+                                                               float *__restrict__ part) {
+  __shared__ float red[4][64];
+  const int cl = threadIdx.x & 63, rl = threadIdx.x >> 6;
+  const int64_t r0 = static_cast<int64_t>(blockIdx.x) * rows_per_block;
+  int64_t r1 = r0 + rows_per_block;
+  if (r1 > T) r1 = T;
+  for (int c0 = 0; c0 < ld; c0 += 64) {
+    const int c = c0 + cl;
+    float s = 0.f;
+    if (c < ld)
+      for (int64_t t = r0 + rl; t < r1; t += 4) s += src[t * ld + c];
     __syncthreads();
+    red[rl][cl] = s;
+    __syncthreads();
+    if (rl == 0 && c < ld)
+      part[static_cast<size_t>(blockIdx.x) * ld + c] = ((red[0][cl] + red[1][cl]) + red[2][cl]) + red[3][cl];
   }
-  if (threadIdx.x == 0) {
-    if (c < nA) dstA[c] = red[0];
-    else dstB[c - nA] = red[0];
+}
+
+__global__ __launch_bounds__(kBlock) void colsum_stage2_kernel(const float *__restrict__ part,
+                                                               int nblocks, int ld, int nA,
+                                                               float *__restrict__ dstA,
+                                                               float *__restrict__ dstB) {
+  for (int c = threadIdx.x; c < ld; c += kBlock) {
+    float s = 0.f;
+    for (int b = 0; b < nblocks; ++b) s += part[static_cast<size_t>(b) * ld + c];
+    if (c < nA) dstA[c] = s;
+    else dstB[c - nA] = s;
   }
 }
 
@@ -701,16 +718,25 @@ hipError_t launch_fill_zero(float *p, size_t count, hipStream_t s) {
   return hipGetLastError();
 }
 
-hipError_t launch_colsum(const float *src, int64_t T, int ld, int cols, float *dst, hipStream_t s) {
-  hipLaunchKernelGGL(colsum_kernel, dim3(cols), dim3(kBlock), 0, s, src, T, ld, cols, dst, dst);
+hipError_t launch_param_sums(const mhcl_desc &d, int M, const float *gz, float *g_b, float *g_alpha,
+                             float *part, hipStream_t s) {
+  const int ld = M + 3;
+  const int nblocks = param_sum_blocks(d);
+  const int64_t rpb = (d.T + nblocks - 1) / nblocks;
+  hipLaunchKernelGGL(colsum_stage1_kernel, dim3(nblocks), dim3(kBlock), 0, s, gz, d.T, ld, rpb,
+                     part);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(colsum_stage2_kernel, dim3(1), dim3(kBlock), 0, s, (const float *)part,
+                     nblocks, ld, M, g_b, g_alpha);
   return hipGetLastError();
 }
 
-hipError_t launch_param_sums(const mhcl_desc &d, int M, const float *gz, float *g_b, float *g_alpha,
-                             hipStream_t s) {
-  hipLaunchKernelGGL(colsum_kernel, dim3(M + 3), dim3(kBlock), 0, s, gz, d.T, M + 3, M, g_b,
-                     g_alpha);
-  return hipGetLastError();
+int param_sum_blocks(const mhcl_desc &d) {
+  int64_t b = (d.T + 127) / 128;
+  if (b > 256) b = 256;
+  if (b < 1) b = 1;
+  return static_cast<int>(b);
 }
 
 }  // namespace mhcl

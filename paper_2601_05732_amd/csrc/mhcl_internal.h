@@ -68,12 +68,11 @@ hipError_t launch_gw_generic(const mhcl_desc &d, int M, const void *x, const flo
 hipError_t launch_copy(void *dst, const void *src, size_t bytes, hipStream_t s);
 // a fill kernel (safe under graph capture, unlike a memset node)
 hipError_t launch_fill_zero(float *p, size_t count, hipStream_t s);
-// dst[c] = sum_t src[t*ld + c], c < cols, fixed order
-hipError_t launch_colsum(const float *src, int64_t T, int ld, int cols, float *dst, hipStream_t s);
-// g_b [M] and g_alpha [3] from gz [T, M+3]
+// g_b [M] and g_alpha [3] from gz [T, M+3]; part is scratch of
+// param_sum_blocks(d) * (M+3) floats
+int param_sum_blocks(const mhcl_desc &d);
 hipError_t launch_param_sums(const mhcl_desc &d, int M, const float *gz, float *g_b, float *g_alpha,
-                             hipStream_t s);
-
+                             float *part, hipStream_t s);
 
 // ---- bf16 fast path (MFMA projections); needs fast_path_ok(desc) ---------
 bool fast_path_ok(const mhcl_desc &d);
@@ -86,7 +85,7 @@ hipError_t launch_proj_mfma(const mhcl_desc &d, int M, const void *x, const void
 bool fast_bwd_ok(const mhcl_desc &d);
 int gw_chunks_fast(const mhcl_desc &d);
 struct FastBwdWs {
-  float *u_raw, *sumsq, *gH_res, *gH_pre, *gH_post, *cpk, *gz, *partials;
+  float *u_raw, *sumsq, *gH_res, *gH_pre, *gH_post, *cpk, *gz, *partials, *psum;
   uint16_t *vr_hi, *vr_lo, *vrT_hi, *vrT_lo;
   char *Wp, *Wa;
   int CP, MP32, MP16;

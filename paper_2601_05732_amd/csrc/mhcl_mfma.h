@@ -35,21 +35,27 @@ __device__ __forceinline__ uint32_t cvt_pk_bf16(float lo, float hi) {
 // Packed layouts of the projection matrix W [K, M] (fp32) as bf16 pairs
 // W = hi + lo (hi = bf16(W), lo = bf16(W - hi): ~16 mantissa bits together).
 //
+// Stream tensors are read in MFMA lane order: at K step s (32 columns) lane
+// (r, q) reads the 16 bytes of token r at columns 32 s + 8 q .. + 7; kernels
+// issue two or more consecutive steps back to back so that the four lanes of a
+// token consume whole 128-byte lines per visit.
+//
 // "B layout" (W as the right operand, contraction over K):
-//   block (s, j, p) for K step s (32 rows), logit tile j (16 columns), part p
-//   (0 = hi, 1 = lo) holds 64 lanes x 8 bf16; lane (r, q), element e is
-//   W[32 s + 8 q + e][16 j + r]  (0 beyond M).  Block index (s*NT + j)*2 + p.
+//   block (s, j, p): K step s (32 rows), logit tile j (16 columns), part p
+//   (0 = hi, 1 = lo); 64 lanes x 8 bf16; lane (r, q), element e is
+//   W[32 s + 8 q + e][16 j + r]  (0 beyond M).  Block index (s * NT + j) * 2 + p.
 //
 // "A layout" (W as the left operand, contraction over the logits):
-//   block (s, h, ms, p): K step s, half h (0/1), logit step ms (32 logits),
-//   part p; lane (r, q), element e is
-//   W[32 s + 8 (r / 4) + 4 h + (r % 4)][32 ms + 8 q + e].
-//   With B = per-token vectors [32 logits x 16 tokens], the two halves leave
-//   lane (token, q) holding rows 32 s + 8 q + 0..3 (h = 0) and + 4..7 (h = 1):
-//   the same 8 consecutive rows that lane loads from a stream tensor.
+//   block (S, h, ms, p): 64-row step S, quarter h = 2 u + hh (u, hh in 0..1),
+//   logit step ms (32 logits), part p; lane (r, q), element e is
+//   W[64 S + 32 u + 8 (r / 4) + 4 hh + (r % 4)][32 ms + 8 q + e].
+//   Block index ((S * 4 + h) * MS + ms) * 2 + p.
+//   With B = per-token vectors [32 logits x 16 tokens], quarter h leaves lane
+//   (token, q) holding rows 64 S + 32 u + 8 q + 4 hh + 0..3: over hh = 0, 1 the
+//   same 8 consecutive rows that lane loads from a stream tensor at step 2 S + u.
 inline int logit_tiles(int M) { return (M + 15) / 16; }
 inline int logit_steps(int M) { return (M + 31) / 32; }
 inline size_t packed_b_bytes(int K, int M) { return static_cast<size_t>(K / 32) * logit_tiles(M) * 2 * 1024; }
-inline size_t packed_a_bytes(int K, int M) { return static_cast<size_t>(K / 32) * 2 * logit_steps(M) * 2 * 1024; }
+inline size_t packed_a_bytes(int K, int M) { return static_cast<size_t>(K / 64) * 4 * logit_steps(M) * 2 * 1024; }
 
 }  // namespace mhcl

@@ -1,0 +1,110 @@
+"""GPU parity at the stated workload sizes, in the launch configuration the
+benchmark times (fused forward calls + fused backward).
+
+The oracle cannot redo a whole 32k-token workload in seconds, so:
+  * per-token outputs (coefficients, h, x_out, g_x, g_y) are compared on a
+    sample of tokens (tile boundaries, first/last, seeded random picks): tokens
+    are independent, so the oracle computes exactly those tokens;
+  * sums over tokens (g_W, g_b, g_alpha) are checked by additivity over a split
+    of the token range at full size, and against the oracle on a 192-token
+    problem of the same n and C;
+  * invariants that hold at any size are checked over all tokens: H_res rows
+    and columns sum to 1 within 1e-6 and stream sums are conserved.
+Tolerances as in test_gpu_parity.py.
+"""
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as si
+from gpu_harness import GpuLayer, desc_for, oracle_reference, rel_err, to_np64
+
+pytestmark = pytest.mark.gpu
+
+FULL = ["n4_c2048_fwd", "n4_c4096", "n3_c1024", "n5_c2560", "n4_c4096_sk"]
+
+
+def _sample_tokens(T, seed=7, extra=12):
+    fixed = [0, 1, 15, 16, 31, 32, 63, 64, 127, 128, 511, 512, T // 2, T - 129, T - 65, T - 2, T - 1]
+    rng = np.random.default_rng(seed)
+    picks = sorted(set(t for t in fixed if 0 <= t < T) | set(rng.integers(0, T, extra).tolist()))
+    return np.array(picks, dtype=np.int64)
+
+
+@pytest.mark.parametrize("name", FULL)
+def test_full_size_sampled_tokens(name):
+    wl = si.WORKLOADS[name]
+    print(f"case {wl}", flush=True)
+    inp = si.make_inputs(wl, seed=0, device="cuda")
+    L = GpuLayer(desc_for(wl), inp)
+    L.forward_fused()
+    if wl.backward:
+        L.backward_fused()
+    torch.cuda.synchronize()
+    tok = _sample_tokens(wl.T)
+    ref = oracle_reference(inp, wl, tokens=tok, backward=wl.backward)
+    idx = torch.as_tensor(tok, device="cuda")
+    for nm, tol in [("H_res", 1e-4), ("H_pre", 1e-4), ("H_post", 1e-4), ("h", 2e-2), ("x_out", 2e-2)]:
+        e = rel_err(to_np64(getattr(L, nm)[idx]), ref[nm])
+        assert e <= tol, f"{nm}: {e:.3e}"
+    if wl.backward:
+        for nm in ("g_x", "g_y"):
+            e = rel_err(to_np64(getattr(L, nm)[idx]), ref[nm])
+            assert e <= 2e-2, f"{nm}: {e:.3e}"
+    # every token: doubly stochastic (permutation form), finite outputs, stream sums conserved
+    H = L.H_res.double()
+    if wl.res_mode == "lite":
+        assert float((H.sum(dim=1) - 1).abs().max()) <= 1e-6
+        assert float((H.sum(dim=2) - 1).abs().max()) <= 1e-6
+        assert float(H.min()) >= 0.0
+    else:
+        assert float((H.sum(dim=2) - 1).abs().max()) <= 1e-5     # SK ends on a row step
+    worst = 0.0
+    for t0 in range(0, wl.T, 4096):
+        sl = slice(t0, min(wl.T, t0 + 4096))
+        lhs = L.x_out[sl].float().sum(dim=1)
+        colsum = L.H_res[sl].sum(dim=1)                         # [t, n]: 1 for doubly stochastic
+        rhs = (inp["x"][sl].float() * colsum[:, :, None]).sum(dim=1) \
+            + L.H_post[sl].sum(dim=1, keepdim=True) * inp["y"][sl].float()
+        worst = max(worst, float((lhs - rhs).abs().max()))
+        assert torch.isfinite(L.x_out[sl].float()).all()
+    assert worst <= wl.n * 2.0 ** -8 * float(L.x_out.float().abs().max())
+    if wl.backward:
+        assert torch.isfinite(L.g_W).all() and torch.isfinite(L.g_x.float()).all()
+
+
+@pytest.mark.parametrize("name", ["n4_c4096", "n3_c1024", "n5_c2560", "n4_c4096_sk"])
+def test_full_size_parameter_gradients(name):
+    wl = si.WORKLOADS[name]
+    print(f"case {wl}", flush=True)
+    inp = si.make_inputs(wl, seed=1, device="cuda")
+    L = GpuLayer(desc_for(wl), inp)
+    L.backward_fused()
+    torch.cuda.synchronize()
+    full = {k: getattr(L, k).double().clone() for k in ("g_W", "g_b", "g_alpha")}
+    # additivity over a ragged split of the tokens (sums over tokens)
+    cut = wl.T // 2 + 37
+    parts = []
+    for sl in (slice(0, cut), slice(cut, wl.T)):
+        sub = {k: (v[sl].contiguous() if k in ("x", "y", "g_xout", "g_h") else v) for k, v in inp.items()}
+        Ls = GpuLayer(desc_for(wl, T=sub["x"].shape[0]), sub)
+        Ls.backward_fused()
+        torch.cuda.synchronize()
+        parts.append({k: getattr(Ls, k).double().clone() for k in ("g_W", "g_b", "g_alpha")})
+        # the split run's per-token outputs equal the full run's, bit for bit
+        assert torch.equal(Ls.g_x, L.g_x[sl]) and torch.equal(Ls.g_y, L.g_y[sl])
+        del Ls
+    for k in full:
+        tot = parts[0][k] + parts[1][k]
+        scale = float(full[k].abs().max())
+        assert float((tot - full[k]).abs().max()) <= 2e-5 * scale, k
+    # oracle on a small-T problem with the same n, C
+    Ts = 192
+    sub = {k: (v[:Ts].contiguous() if k in ("x", "y", "g_xout", "g_h") else v) for k, v in inp.items()}
+    Ls = GpuLayer(desc_for(wl, T=Ts), sub)
+    Ls.backward_fused()
+    torch.cuda.synchronize()
+    ref = oracle_reference(sub, wl)
+    for k in ("g_W", "g_b", "g_alpha"):
+        e = rel_err(to_np64(getattr(Ls, k)), ref[k])
+        assert e <= 2e-3, f"{k}: {e:.3e}"
