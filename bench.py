@@ -110,6 +110,9 @@ def main():
     ap.add_argument("--cpu-sample", type=int, default=16384)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--detail", action="store_true", help="per-stage times on stderr")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run the library's plain copy kernel on 1 GiB five times (a dispatch "
+                         "of known traffic, to scale hardware byte counters with)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (tokens are independent, so the path "
@@ -146,6 +149,28 @@ def main():
         arm(stage in (4, 5, 6))
         mhcl.mhcl_bwd_fused(dd, i["x"], i["y"], i["W"], i["b"], i["alpha"], i["g_xout"], i["g_h"],
                             L.g_x, L.g_y, L.g_W, L.g_b, L.g_alpha, L.ws)
+
+    if args.copy_calibration:
+        lib.mhcl_debug_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t,
+                                        ctypes.c_void_p]
+        nbytes = 1 << 30
+        src = torch.empty(nbytes, dtype=torch.uint8, device="cuda:0").fill_(1)
+        dst = torch.empty_like(src)
+        cev = HipEvents(2)
+        rt = cev.rt
+        rt.hipEventRecord.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
+        stream = torch.cuda.current_stream().cuda_stream
+        for it in range(5):
+            if it == 1:
+                rt.hipEventRecord(cev.ev[0], stream)
+            lib.mhcl_debug_copy(dst.data_ptr(), src.data_ptr(), nbytes, stream)
+        rt.hipEventRecord(cev.ev[1], stream)
+        torch.cuda.synchronize()
+        ms = cev.elapsed_ms(0, 1) / 4
+        print(f"[copy] 1 GiB device copy: {ms:.3f} ms, {2 * nbytes / ms / 1e6:.1f} GB/s "
+              "(read + write)", file=sys.stderr)
+        cev.close()
+        del src, dst
 
     # warmup; the last warmup passes also find the stage that takes longest
     probe = HipEvents(2)

@@ -499,11 +499,23 @@ __global__ __launch_bounds__(kBlock) void colsum_stage2_kernel(const float *__re
                                                                int nblocks, int ld, int nA,
                                                                float *__restrict__ dstA,
                                                                float *__restrict__ dstB) {
-  for (int c = threadIdx.x; c < ld; c += kBlock) {
+  __shared__ float red[4][64];
+  const int cl = threadIdx.x & 63, rl = threadIdx.x >> 6;
+  for (int c0 = 0; c0 < ld; c0 += 64) {
+    const int c = c0 + cl;
     float s = 0.f;
-    for (int b = 0; b < nblocks; ++b) s += part[static_cast<size_t>(b) * ld + c];
-    if (c < nA) dstA[c] = s;
-    else dstB[c - nA] = s;
+    if (c < ld) {
+#pragma unroll 8
+      for (int b = rl; b < nblocks; b += 4) s += part[static_cast<size_t>(b) * ld + c];
+    }
+    __syncthreads();
+    red[rl][cl] = s;
+    __syncthreads();
+    if (rl == 0 && c < ld) {
+      const float v = ((red[0][cl] + red[1][cl]) + red[2][cl]) + red[3][cl];
+      if (c < nA) dstA[c] = v;
+      else dstB[c - nA] = v;
+    }
   }
 }
 
