@@ -36,8 +36,8 @@ def stage_bytes(stage: int, n: int, C: int, T: int, e: int) -> int:
         2: (n + 1) * U,          # read x, write h
         3: (2 * n + 1) * U,      # read x, y; write x_out
         4: (2 * n + 2) * U,      # read x, g_xout, y, g_h
-        5: (3 * n + 2) * U,      # read x, g_xout, g_h; write g_x, g_y
-        6: n * U,                # read x (g_W itself is MiBs)
+        5: (3 * n + 2) * U,      # read x, g_xout, g_h; write g_x, g_y (g_W rides on the same read)
+        6: n * U,                # separate g_W kernel (paths where it is not fused): read x
     }[stage]
     return per_token * T
 
@@ -71,6 +71,7 @@ class HipEvents:
         ms = ctypes.c_float()
         rc = self.rt.hipEventElapsedTime(ctypes.byref(ms), self.ev[i], self.ev[j])
         if rc != 0:
+            self.rt.hipGetLastError()     # reset the runtime's sticky error state
             raise RuntimeError(f"hipEventElapsedTime failed ({rc})")
         return ms.value
 
@@ -173,14 +174,17 @@ def main():
         del src, dst
 
     # warmup; the last warmup passes also find the stage that takes longest
-    probe = HipEvents(2)
+    probe = HipEvents(2 * len(STAGES))
     for _ in range(max(0, args.warmup - len(STAGES))):
         step()
     stage_ms = {}
-    for st in STAGES:
-        step(st, probe, 0)
+    for i, st in enumerate(STAGES):
+        step(st, probe, 2 * i)
         torch.cuda.synchronize()
-        stage_ms[st] = probe.elapsed_ms(0, 1)
+        try:
+            stage_ms[st] = probe.elapsed_ms(2 * i, 2 * i + 1)
+        except RuntimeError:
+            pass          # this stage is fused into another kernel for this workload
     probe.close()
     dominant = max(stage_ms, key=stage_ms.get)
     if args.detail:

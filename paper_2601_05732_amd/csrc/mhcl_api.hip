@@ -41,8 +41,9 @@ struct CoeffsWs {
   CoeffsWs(const mhcl_desc &d, void *ws) {
     WsCursor c(ws);
     const size_t T = static_cast<size_t>(d.T);
-    u_raw = c.take<float>(T * logits(d));
-    sumsq = c.take<float>(T);
+    const size_t parts = static_cast<size_t>(proj_ksplit(d));
+    u_raw = c.take<float>(parts * T * logits(d));
+    sumsq = c.take<float>(parts * T);
     Wp = fast_path_ok(d) ? c.take<char>(packed_w_b_bytes(d, logits(d))) : nullptr;
     bytes = c.off;
   }
@@ -57,8 +58,9 @@ struct BwdWs {
     WsCursor c(ws);
     const size_t T = static_cast<size_t>(d.T);
     const int M = logits(d), n = d.n;
-    u_raw = c.take<float>(T * M);
-    sumsq = c.take<float>(T);
+    const size_t parts = static_cast<size_t>(proj_ksplit(d));
+    u_raw = c.take<float>(parts * T * M);
+    sumsq = c.take<float>(parts * T);
     tok.H_res = c.take<float>(T * n * n);
     tok.H_pre = c.take<float>(T * n);
     tok.H_post = c.take<float>(T * n);
@@ -200,7 +202,7 @@ int mhcl_coeffs(const mhcl_desc *desc, const void *x, const float *W, const floa
   CoeffsWs w(*desc, ws);
   Disarm disarm;
   MHCL_HIP(run_projection(*desc, x, W, w.u_raw, w.sumsq, w.Wp, MHCL_STAGE_FWD_PROJ, s));
-  MHCL_HIP(launch_coeffs_epilogue(*desc, w.u_raw, w.sumsq, b, alpha, H_res, H_pre, H_post, s));
+  MHCL_HIP(launch_coeffs_epilogue(*desc, proj_ksplit(*desc), w.u_raw, w.sumsq, b, alpha, H_res, H_pre, H_post, s));
   return MHCL_OK;
 }
 
@@ -241,7 +243,7 @@ int mhcl_fwd_coeffs_pre(const mhcl_desc *desc, const void *x, const float *W, co
   CoeffsWs w(*desc, ws);
   Disarm disarm;
   MHCL_HIP(run_projection(*desc, x, W, w.u_raw, w.sumsq, w.Wp, MHCL_STAGE_FWD_PROJ, s));
-  MHCL_HIP(launch_coeffs_epilogue(*desc, w.u_raw, w.sumsq, b, alpha, H_res, H_pre, H_post, s));
+  MHCL_HIP(launch_coeffs_epilogue(*desc, proj_ksplit(*desc), w.u_raw, w.sumsq, b, alpha, H_res, H_pre, H_post, s));
   {
     StageBracket br(MHCL_STAGE_FWD_PRE, s);
     MHCL_HIP(launch_pre(*desc, x, H_pre, h, s));
@@ -298,7 +300,7 @@ int mhcl_coeffs_bwd(const mhcl_desc *desc, const void *x, const float *W, const 
   BwdWs w(*desc, ws, false);
   Disarm disarm;
   MHCL_HIP(run_projection(*desc, x, W, w.u_raw, w.sumsq, w.Wp, MHCL_STAGE_BWD_REDUCE, s));
-  MHCL_HIP(launch_coeffs_bwd_epilogue(*desc, w.u_raw, w.sumsq, b, alpha, g_H_res, g_H_pre,
+  MHCL_HIP(launch_coeffs_bwd_epilogue(*desc, proj_ksplit(*desc), w.u_raw, w.sumsq, b, alpha, g_H_res, g_H_pre,
                                       g_H_post, w.tok, s));
   MHCL_HIP(launch_gx_generic(*desc, M, false, x, W, nullptr, nullptr, w.tok, g_x, nullptr, s));
   MHCL_HIP(launch_gw_generic(*desc, M, x, w.tok.vr, w.partials, g_W, s));
@@ -341,11 +343,7 @@ int mhcl_bwd_fused(const mhcl_desc *desc, const void *x, const void *y, const fl
     MHCL_HIP(launch_bwd_epilogue_fast(*desc, b, alpha, f, s));
     {
       StageBracket br(MHCL_STAGE_BWD_OUT, s);
-      MHCL_HIP(launch_bwd_out(*desc, x, g_xout, g_h, f, g_x, g_y, s));
-    }
-    {
-      StageBracket br(MHCL_STAGE_BWD_GW, s);
-      MHCL_HIP(launch_bwd_gw(*desc, M, x, f, g_W, s));
+      MHCL_HIP(launch_bwd_out_gw(*desc, M, x, g_xout, g_h, f, g_x, g_y, g_W, s));
     }
     MHCL_HIP(launch_param_sums(*desc, M, f.gz, g_b, g_alpha, f.psum, s));
     return MHCL_OK;
@@ -353,7 +351,7 @@ int mhcl_bwd_fused(const mhcl_desc *desc, const void *x, const void *y, const fl
   BwdWs w(*desc, ws, true);
   MHCL_HIP(run_projection(*desc, x, W, w.u_raw, w.sumsq, w.Wp, MHCL_STAGE_BWD_REDUCE, s));
   MHCL_HIP(launch_bwd_dots(*desc, x, y, g_xout, g_h, w.gH_res, w.gH_post, w.gH_pre, s));
-  MHCL_HIP(launch_coeffs_bwd_epilogue(*desc, w.u_raw, w.sumsq, b, alpha, w.gH_res, w.gH_pre,
+  MHCL_HIP(launch_coeffs_bwd_epilogue(*desc, proj_ksplit(*desc), w.u_raw, w.sumsq, b, alpha, w.gH_res, w.gH_pre,
                                       w.gH_post, w.tok, s));
   {
     StageBracket br(MHCL_STAGE_BWD_OUT, s);

@@ -54,7 +54,15 @@ __global__ __launch_bounds__(256) void pack_w_b_kernel(const float *__restrict__
 // the A tile as both operands.
 template <int NT>
 struct ProjCfg {
-  static constexpr int KC = NT == 2 ? 8 : (NT == 9 ? 2 : 4);   // K steps per chunk
+#ifndef MHCL_PROJ_KC
+#define MHCL_PROJ_KC 4
+#endif
+#ifndef MHCL_PROJ_TG
+#define MHCL_PROJ_TG 2
+#endif
+  static constexpr int KC = NT == 2 ? MHCL_PROJ_KC : (NT == 9 ? 2 : 4);   // K steps per chunk
+  static constexpr int TG = NT == 2 ? MHCL_PROJ_TG : 2;        // 16-token A tiles per wave
+  static constexpr int kTokens = 64 * TG;                      // tokens per block
   static constexpr int kChunkVec = KC * NT * 2 * 64;           // u32x4 per chunk
   static constexpr int kLdsBytes = 2 * kChunkVec * 16;
 };
@@ -65,12 +73,15 @@ __global__ __launch_bounds__(256, 2) void proj_mfma_kernel(const uint16_t *__res
                                                            int M, int64_t T,
                                                            float *__restrict__ u_raw,
                                                            float *__restrict__ sumsq) {
+  // gridDim.y blocks share the K range of the same tokens (K split): block
+  // (bx, part) walks K steps [part * nsteps, (part + 1) * nsteps) and writes its
+  // partial u_raw / sumsq to slice `part`; the consumer adds the slices in order.
   using Cfg = ProjCfg<NT>;
-  constexpr int KC = Cfg::KC, TG = 2;
+  constexpr int KC = Cfg::KC, TG = Cfg::TG;
   extern __shared__ u32x4 lds[];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int r = lane & 15, q = lane >> 4;
-  const int64_t tw = static_cast<int64_t>(blockIdx.x) * 128 + wave * 32;
+  const int64_t tw = static_cast<int64_t>(blockIdx.x) * Cfg::kTokens + wave * (16 * TG);
   const uint16_t *row[TG];
 #pragma unroll
   for (int g = 0; g < TG; ++g) {
@@ -78,7 +89,13 @@ __global__ __launch_bounds__(256, 2) void proj_mfma_kernel(const uint16_t *__res
     if (t > T - 1) t = T - 1;
     row[g] = x + t * K + q * 8;
   }
-  const int nsteps = K / 32;
+  const int nsteps = K / 32 / gridDim.y;          // K steps of this block
+  const int step0 = blockIdx.y * nsteps;
+#pragma unroll
+  for (int g = 0; g < TG; ++g) row[g] += static_cast<size_t>(step0) * 32;
+  Wp += static_cast<size_t>(step0) * NT * 2 * 64;
+  u_raw += static_cast<size_t>(blockIdx.y) * T * M;
+  sumsq += static_cast<size_t>(blockIdx.y) * T;
   const int nchunks = (nsteps + KC - 1) / KC;
 
   f32x4 acc[TG][NT], ss[TG];
@@ -624,6 +641,250 @@ __global__ __launch_bounds__(256, 2) void bwd_out_kernel(
 }
 
 // ---------------------------------------------------------------------------
+// Backward pass 2, fused: bwd_out_kernel's outputs AND g_W from the same read of
+// x (n <= 4, one wave per stream).  Per block iteration the four waves load the
+// tiles of 4 x 16 tokens as above, publish their x tiles in LDS, and wave w
+// then accumulates g_W rows of stream w for all 64 tokens:
+//   D[m][k] += vrT[m][token] * x^T[token][k]
+// with x^T obtained by an MFMA against a 0/1 selection matrix (exact) as in
+// bwd_gw_kernel.  Accumulators stay in registers over the block's token chunk;
+// partial sums per chunk go to `gw_part` and are added in chunk order.
+template <int N, int NT>
+__global__ __launch_bounds__(256, 2) void bwd_out_gw_kernel(
+    const uint16_t *__restrict__ x, const uint16_t *__restrict__ g,
+    const uint16_t *__restrict__ gh, const u32x4 *__restrict__ Wa, const float *__restrict__ cpk,
+    const uint16_t *__restrict__ vr_hi, const uint16_t *__restrict__ vr_lo,
+    const uint16_t *__restrict__ vrT_hi, const uint16_t *__restrict__ vrT_lo, int MP16, int M, int C,
+    int64_t T, int tokens_per_block, int CP, uint16_t *__restrict__ g_x,
+    uint16_t *__restrict__ g_y, float *__restrict__ gw_part) {
+  constexpr int NCP = N * N + 2 * N + 1;
+  constexpr int NCP4 = (NCP + 3) / 4;
+  constexpr int kSliceVec = N * 4 * 2 * 64;   // 16-byte words of W per 64-column step
+  extern __shared__ u32x4 lds[];
+  u32x4 *xch = lds + kSliceVec;               // x tiles of one iteration: [stream][wave][u][lane]
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int r = lane & 15, q = lane >> 4;
+  const int S = blockIdx.x;
+  const int c0 = S * 64 + q * 8;
+  const int nS = C / 64;
+  for (int e = threadIdx.x; e < kSliceVec; e += 256) {
+    const int j = e / 512, rem = e % 512;
+    lds[e] = Wa[static_cast<size_t>(j * nS + S) * 512 + rem];
+  }
+  const u32x4 *wl = lds + lane;
+
+  const int64_t tb = static_cast<int64_t>(blockIdx.y) * tokens_per_block;   // multiple of 64
+  int64_t te = tb + tokens_per_block;
+  if (te > T) te = T;
+
+  u32x4 sel[2];   // selection operands: column c of half h picks row 16 h + c
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    uint32_t w[4];
+#pragma unroll
+    for (int e2 = 0; e2 < 4; ++e2) {
+      const int k0 = 8 * q + 2 * e2, k1 = k0 + 1;
+      w[e2] = (k0 == 16 * h + r ? 0x3F80u : 0u) | (k1 == 16 * h + r ? 0x3F800000u : 0u);
+    }
+    sel[h] = u32x4{w[0], w[1], w[2], w[3]};
+  }
+  f32x4 acc[2][2][NT];
+#pragma unroll
+  for (int u = 0; u < 2; ++u)
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+      for (int mt = 0; mt < NT; ++mt) acc[u][h][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  auto unpack = [](const u32x4 &v, float (&o)[8]) {
+    o[0] = bf16lo(v.x); o[1] = bf16hi(v.x); o[2] = bf16lo(v.y); o[3] = bf16hi(v.y);
+    o[4] = bf16lo(v.z); o[5] = bf16hi(v.z); o[6] = bf16lo(v.w); o[7] = bf16hi(v.w);
+  };
+  auto pack = [](const float (&o)[8]) {
+    u32x4 v;
+    v.x = cvt_pk_bf16(o[0], o[1]); v.y = cvt_pk_bf16(o[2], o[3]);
+    v.z = cvt_pk_bf16(o[4], o[5]); v.w = cvt_pk_bf16(o[6], o[7]);
+    return v;
+  };
+
+  struct In {
+    u32x4 X[N][2], G[N][2], H[2], vbh, vbl;
+    float4 cp[NCP4];
+  };
+  auto load_x = [&](In &in, int64_t t0) {
+    int64_t tl = t0 + r;
+    if (tl > te - 1) tl = te - 1;
+#pragma unroll
+    for (int j = 0; j < N; ++j)
+#pragma unroll
+      for (int u = 0; u < 2; ++u)
+        in.X[j][u] = *reinterpret_cast<const u32x4 *>(x + (tl * N + j) * C + c0 + u * 32);
+  };
+  auto load_rest = [&](In &in, int64_t t0) {
+    int64_t tl = t0 + r;
+    if (tl > te - 1) tl = te - 1;
+#pragma unroll
+    for (int j = 0; j < N; ++j)
+#pragma unroll
+      for (int u = 0; u < 2; ++u)
+        in.G[j][u] = *reinterpret_cast<const u32x4 *>(g + (tl * N + j) * C + c0 + u * 32);
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+      in.H[u] = *reinterpret_cast<const u32x4 *>(gh + tl * C + c0 + u * 32);
+    in.vbh = *reinterpret_cast<const u32x4 *>(vr_hi + tl * 32 + q * 8);
+    in.vbl = *reinterpret_cast<const u32x4 *>(vr_lo + tl * 32 + q * 8);
+    const float4 *cpp = reinterpret_cast<const float4 *>(cpk + tl * CP);
+#pragma unroll
+    for (int e = 0; e < NCP4; ++e) in.cp[e] = cpp[e];
+  };
+  auto process = [&](const In &in, int64_t t0) {
+    const int64_t t = t0 + r;
+    const bool live = t < te;
+    float cp[NCP4 * 4];
+#pragma unroll
+    for (int e = 0; e < NCP4; ++e) {
+      cp[4 * e] = in.cp[e].x; cp[4 * e + 1] = in.cp[e].y;
+      cp[4 * e + 2] = in.cp[e].z; cp[4 * e + 3] = in.cp[e].w;
+    }
+    const float cx = cp[N * N + 2 * N];
+    float gv[2][N][8], hv[2][8];
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+#pragma unroll
+      for (int i = 0; i < N; ++i) unpack(in.G[i][u], gv[u][i]);
+      unpack(in.H[u], hv[u]);
+    }
+    {   // g_y
+      u32x4 ov[2];
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        float o[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          float sacc = 0.f;
+#pragma unroll
+          for (int i = 0; i < N; ++i) sacc += cp[N * N + N + i] * gv[u][i][e];
+          o[e] = sacc;
+        }
+        ov[u] = pack(o);
+      }
+      if (live) {
+        *reinterpret_cast<u32x4 *>(g_y + t * C + c0) = ov[0];
+        *reinterpret_cast<u32x4 *>(g_y + t * C + c0 + 32) = ov[1];
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < N; ++j) {
+      u32x4 ov[2];
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        f32x4 wv[2];
+#pragma unroll
+        for (int hh = 0; hh < 2; ++hh) {
+          const int h = 2 * u + hh;
+          const u32x4 wh = wl[((j * 4 + h) * 2 + 0) * 64], wlo = wl[((j * 4 + h) * 2 + 1) * 64];
+          wv[hh] = mfma16(wh, in.vbh, f32x4{0.f, 0.f, 0.f, 0.f});
+          wv[hh] = mfma16(wlo, in.vbh, wv[hh]);
+          wv[hh] = mfma16(wh, in.vbl, wv[hh]);
+        }
+        float xv[8], o[8];
+        unpack(xch[((j * 4 + wave) * 2 + u) * 64 + lane], xv);   // this wave's own tile, parked in LDS
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          float sacc = wv[e >> 2][e & 3] - xv[e] * cx;
+#pragma unroll
+          for (int i = 0; i < N; ++i) sacc += cp[i * N + j] * gv[u][i][e];
+          sacc += cp[N * N + j] * hv[u][e];
+          o[e] = sacc;
+        }
+        ov[u] = pack(o);
+      }
+      if (live) {
+        *reinterpret_cast<u32x4 *>(g_x + (t * N + j) * C + c0) = ov[0];
+        *reinterpret_cast<u32x4 *>(g_x + (t * N + j) * C + c0 + 32) = ov[1];
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+  // g_W rows of stream `wave` from the 64 tokens whose x tiles sit in LDS
+  auto gw_accumulate = [&](int64_t t0blk) {
+    const int64_t blk0 = t0blk >> 5;   // two 32-token blocks of vrT
+#pragma unroll
+    for (int pr = 0; pr < 2; ++pr) {   // wave pairs (0,1) and (2,3) = one 32-token block each
+      u32x4 va[NT][2];
+#pragma unroll
+      for (int mt = 0; mt < NT; ++mt) {
+        const size_t row = (static_cast<size_t>(blk0 + pr) * MP16 + mt * 16 + r) * 32;
+        const u32x2 h0 = *reinterpret_cast<const u32x2 *>(vrT_hi + row + 4 * q);
+        const u32x2 h1 = *reinterpret_cast<const u32x2 *>(vrT_hi + row + 16 + 4 * q);
+        const u32x2 l0 = *reinterpret_cast<const u32x2 *>(vrT_lo + row + 4 * q);
+        const u32x2 l1 = *reinterpret_cast<const u32x2 *>(vrT_lo + row + 16 + 4 * q);
+        va[mt][0] = u32x4{h0.x, h0.y, h1.x, h1.y};
+        va[mt][1] = u32x4{l0.x, l0.y, l1.x, l1.y};
+      }
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        const u32x4 xa = xch[((wave * 4 + 2 * pr + 0) * 2 + u) * 64 + lane];
+        const u32x4 xb = xch[((wave * 4 + 2 * pr + 1) * 2 + u) * 64 + lane];
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+          const f32x4 z = f32x4{0.f, 0.f, 0.f, 0.f};
+          const f32x4 ta = mfma16(xa, sel[h], z);   // tokens 4q+i of the pair's first 16
+          const f32x4 tb2 = mfma16(xb, sel[h], z);  // tokens 4q+i of its second 16
+          u32x4 bt;
+          bt.x = cvt_pk_bf16(ta[0], ta[1]); bt.y = cvt_pk_bf16(ta[2], ta[3]);
+          bt.z = cvt_pk_bf16(tb2[0], tb2[1]); bt.w = cvt_pk_bf16(tb2[2], tb2[3]);
+#pragma unroll
+          for (int mt = 0; mt < NT; ++mt) {
+            acc[u][h][mt] = mfma16(va[mt][0], bt, acc[u][h][mt]);
+            acc[u][h][mt] = mfma16(va[mt][1], bt, acc[u][h][mt]);
+          }
+        }
+      }
+    }
+  };
+
+  // Per iteration: the x tiles go to LDS as soon as they arrive, which frees
+  // their registers for the NEXT iteration's x tiles; those are requested right
+  // away and fly while this iteration's g_W and mixing work runs.
+  In in;
+  const int niter = static_cast<int>((te - tb + 63) / 64);   // same for all four waves
+  load_x(in, tb + wave * 16);
+  for (int it = 0; it < niter; ++it) {
+    const int64_t t0 = tb + static_cast<int64_t>(it) * 64 + wave * 16;
+    load_rest(in, t0);
+    __syncthreads();   // everyone is done with the previous iteration's x tiles (and W is staged)
+#pragma unroll
+    for (int j = 0; j < N; ++j)
+#pragma unroll
+      for (int u = 0; u < 2; ++u) xch[((j * 4 + wave) * 2 + u) * 64 + lane] = in.X[j][u];
+    __syncthreads();
+    load_x(in, t0 + 64);   // clamped to the block's last token when past the end
+    __builtin_amdgcn_sched_barrier(0);
+    if (wave < N) gw_accumulate(tb + static_cast<int64_t>(it) * 64);
+    __builtin_amdgcn_sched_barrier(0);
+    process(in, t0);
+  }
+
+  if (wave < N) {
+    float *dst = gw_part + static_cast<size_t>(blockIdx.y) * (static_cast<size_t>(N) * C) * M;
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const int k = wave * C + S * 64 + u * 32 + 16 * h + r;
+#pragma unroll
+        for (int mt = 0; mt < NT; ++mt)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const int m = mt * 16 + 4 * q + i;
+            if (m < M) dst[static_cast<size_t>(k) * M + m] = acc[u][h][mt][i];
+          }
+      }
+  }
+}
+
+// ---------------------------------------------------------------------------
 // Backward pass 2b: g_W[k][m] = sum_t x_hat[t][k] vr[t][m], the one reduction
 // over tokens.  A wave owns CSW K steps (32 rows of g_W each) and walks a chunk
 // of tokens 32 at a time.  x arrives with tokens across lanes, but the
@@ -771,9 +1032,27 @@ hipError_t launch_pack_w_b(const mhcl_desc &d, int M, const float *W, void *Wp, 
   return hipGetLastError();
 }
 
+int proj_ksplit(const mhcl_desc &d) {
+  if (!fast_path_ok(d)) return 1;
+  const int M = res_logits(d.n, d.res_mode) + 2 * d.n;
+  int kc = 4, tok = 128;
+  switch (logit_tiles(M)) {
+    case 1: kc = ProjCfg<1>::KC; tok = ProjCfg<1>::kTokens; break;
+    case 2: kc = ProjCfg<2>::KC; tok = ProjCfg<2>::kTokens; break;
+    case 3: kc = ProjCfg<3>::KC; tok = ProjCfg<3>::kTokens; break;
+    case 9: kc = ProjCfg<9>::KC; tok = ProjCfg<9>::kTokens; break;
+  }
+  const int nsteps = d.n * d.C / 32;
+  const int64_t blocks = (d.T + tok - 1) / tok;
+  int ks = 1;   // enough blocks for two per CU, each part a whole number of chunk pairs
+  while (ks < kMaxKSplit && blocks * ks < 512 && nsteps % (ks * 2 * 2 * kc) == 0) ks *= 2;
+  return ks;
+}
+
 hipError_t launch_proj_mfma(const mhcl_desc &d, int M, const void *x, const void *Wp, float *u_raw,
                             float *sumsq, hipStream_t s) {
   const int K = d.n * d.C;
+  const int ks = proj_ksplit(d);
   return dispatch_nt(logit_tiles(M), [&](auto nt) {
     constexpr int NT = decltype(nt)::value;
     auto kern = proj_mfma_kernel<NT>;
@@ -783,9 +1062,10 @@ hipError_t launch_proj_mfma(const mhcl_desc &d, int M, const void *x, const void
                                          hipFuncAttributeMaxDynamicSharedMemorySize, lds);
       if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>((d.T + 127) / 128)), dim3(256), lds, s,
-                       static_cast<const uint16_t *>(x), static_cast<const u32x4 *>(Wp), K, M, d.T,
-                       u_raw, sumsq);
+    constexpr int kTok = ProjCfg<NT>::kTokens;
+    hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>((d.T + kTok - 1) / kTok), ks), dim3(256),
+                       lds, s, static_cast<const uint16_t *>(x), static_cast<const u32x4 *>(Wp), K,
+                       M, d.T, u_raw, sumsq);
     return hipGetLastError();
   });
 }
@@ -798,6 +1078,13 @@ namespace {
 int gw_xblocks(const mhcl_desc &d) { return (d.n * d.C / 32 + 15) / 16; }   // 4 waves x 4 K steps
 }  // namespace
 
+int out_gw_tokens_per_block(const mhcl_desc &d) {
+  // at most 16 partial copies of g_W, blocks of a whole number of 64-token iterations
+  int64_t tpb = ((d.T + 15) / 16 + 63) / 64 * 64;
+  if (tpb < 512) tpb = 512;
+  return static_cast<int>(tpb);
+}
+
 int gw_chunks_fast(const mhcl_desc &d) {
   const int64_t nblk = (d.T + 31) / 32;
   int64_t c = (512 + gw_xblocks(d) - 1) / gw_xblocks(d);
@@ -809,7 +1096,7 @@ int gw_chunks_fast(const mhcl_desc &d) {
 
 FastBwdWs::FastBwdWs(const mhcl_desc &d, void *ws) {
   WsCursor c(ws);
-  const size_t T = static_cast<size_t>(d.T), Tpad = (T + 31) / 32 * 32;
+  const size_t T = static_cast<size_t>(d.T), Tpad = (T + 63) / 64 * 64;
   const int n = d.n, M = res_logits(d.n, d.res_mode) + 2 * d.n, K = d.n * d.C;
   CP = 32;
   MP32 = logit_steps(M) * 32;
@@ -827,7 +1114,12 @@ FastBwdWs::FastBwdWs(const mhcl_desc &d, void *ws) {
   vrT_lo = c.take<uint16_t>(Tpad * MP16);
   Wp = c.take<char>(packed_b_bytes(K, M));
   Wa = c.take<char>(packed_a_bytes(K, M));
-  partials = c.take<float>(static_cast<size_t>(gw_chunks_fast(d)) * K * M);
+  {
+    const int64_t tpb = out_gw_tokens_per_block(d);
+    const size_t fused_chunks = static_cast<size_t>((d.T + tpb - 1) / tpb);
+    const size_t chunks = fused_chunks > static_cast<size_t>(gw_chunks_fast(d)) ? fused_chunks : gw_chunks_fast(d);
+    partials = c.take<float>(chunks * K * M);
+  }
   psum = c.take<float>(static_cast<size_t>(param_sum_blocks(d)) * (M + 3));
   bytes = c.off;
 }
@@ -869,7 +1161,7 @@ hipError_t launch_bwd_reduce(const mhcl_desc &d, int M, const void *x, const voi
 
 hipError_t launch_bwd_epilogue_fast(const mhcl_desc &d, const float *b, const float *alpha,
                                     const FastBwdWs &w, hipStream_t s) {
-  const int64_t Tpad = (d.T + 31) / 32 * 32;
+  const int64_t Tpad = (d.T + 63) / 64 * 64;
   auto go = [&](auto nn, auto mm) {
     constexpr int N = decltype(nn)::value, MODE = decltype(mm)::value;
     hipLaunchKernelGGL((bwd_epilogue_fast_kernel<N, MODE>),
@@ -932,6 +1224,40 @@ hipError_t launch_bwd_gw(const mhcl_desc &d, int M, const void *x, const FastBwd
       return hipErrorInvalidValue;
     }
   });
+  if (e != hipSuccess || chunks == 1) return e;
+  return launch_sum_partials(w.partials, static_cast<size_t>(K) * M, chunks, g_W, s);
+}
+
+
+// g_x, g_y and g_W from one pass (n <= 4)
+hipError_t launch_bwd_out_gw(const mhcl_desc &d, int M, const void *x, const void *g_xout,
+                             const void *g_h, const FastBwdWs &w, void *g_x, void *g_y, float *g_W,
+                             hipStream_t s) {
+  const int K = d.n * d.C;
+  const int tpb = out_gw_tokens_per_block(d);
+  const int chunks = static_cast<int>((d.T + tpb - 1) / tpb);
+  float *dst = chunks == 1 ? g_W : w.partials;
+  auto go = [&](auto nn, auto nt) {
+    constexpr int N = decltype(nn)::value, NT = decltype(nt)::value;
+    constexpr int lds = (N * 4 * 2 * 64) * 2 * 16;
+    hipLaunchKernelGGL((bwd_out_gw_kernel<N, NT>), dim3(d.C / 64, chunks), dim3(256), lds, s,
+                       static_cast<const uint16_t *>(x), static_cast<const uint16_t *>(g_xout),
+                       static_cast<const uint16_t *>(g_h), reinterpret_cast<const u32x4 *>(w.Wa),
+                       w.cpk, w.vr_hi, w.vr_lo, w.vrT_hi, w.vrT_lo, w.MP16, M, d.C, d.T, tpb, w.CP,
+                       static_cast<uint16_t *>(g_x), static_cast<uint16_t *>(g_y), dst);
+    return hipGetLastError();
+  };
+  using I1 = std::integral_constant<int, 1>;
+  using I2 = std::integral_constant<int, 2>;
+  using I3 = std::integral_constant<int, 3>;
+  using I4 = std::integral_constant<int, 4>;
+  hipError_t e = hipErrorInvalidValue;
+  switch (d.n * 10 + logit_tiles(M)) {
+    case 11: e = go(I1{}, I1{}); break;
+    case 21: e = go(I2{}, I1{}); break;
+    case 31: e = go(I3{}, I1{}); break;
+    case 42: e = go(I4{}, I2{}); break;
+  }
   if (e != hipSuccess || chunks == 1) return e;
   return launch_sum_partials(w.partials, static_cast<size_t>(K) * M, chunks, g_W, s);
 }

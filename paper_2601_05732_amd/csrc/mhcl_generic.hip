@@ -113,17 +113,23 @@ __global__ __launch_bounds__(kBlock) void proj_generic_kernel(const void *__rest
 // ------------------------------------------------------------ coefficients
 template <int N, int MODE>
 __global__ __launch_bounds__(128) void coeffs_epilogue_kernel(
-    const float *__restrict__ u_raw, const float *__restrict__ sumsq, const float *__restrict__ b,
-    const float *__restrict__ alpha, int nC, float eps, int sk_iters, int64_t T,
-    float *__restrict__ H_res, float *__restrict__ H_pre, float *__restrict__ H_post) {
+    const float *__restrict__ u_raw, const float *__restrict__ sumsq, int parts,
+    const float *__restrict__ b, const float *__restrict__ alpha, int nC, float eps, int sk_iters,
+    int64_t T, float *__restrict__ H_res, float *__restrict__ H_pre, float *__restrict__ H_post) {
   constexpr int R = Dims<N, MODE>::R, M = Dims<N, MODE>::M;
   const int64_t t = static_cast<int64_t>(blockIdx.x) * 128 + threadIdx.x;
   if (t >= T) return;
   float u[M], bb[M], a[R], Hr[N * N], Hp[N], Hq[N];
+  float ssq = sumsq[t];
 #pragma unroll
   for (int m = 0; m < M; ++m) { u[m] = u_raw[t * M + m]; bb[m] = b[m]; }
+  for (int pt = 1; pt < parts; ++pt) {   // K-split slices, added in order
+    ssq += sumsq[pt * T + t];
+#pragma unroll
+    for (int m = 0; m < M; ++m) u[m] += u_raw[(pt * T + t) * M + m];
+  }
   const TokenParams p{alpha[0], alpha[1], alpha[2], eps, sk_iters};
-  token_coeffs<N, MODE>(u, sumsq[t], nC, bb, p, Hr, Hp, Hq, a);
+  token_coeffs<N, MODE>(u, ssq, nC, bb, p, Hr, Hp, Hq, a);
 #pragma unroll
   for (int e = 0; e < N * N; ++e) H_res[t * N * N + e] = Hr[e];
 #pragma unroll
@@ -132,8 +138,8 @@ __global__ __launch_bounds__(128) void coeffs_epilogue_kernel(
 
 template <int N, int MODE>
 __global__ __launch_bounds__(128) void coeffs_bwd_epilogue_kernel(
-    const float *__restrict__ u_raw, const float *__restrict__ sumsq, const float *__restrict__ b,
-    const float *__restrict__ alpha, const float *__restrict__ gH_res,
+    const float *__restrict__ u_raw, const float *__restrict__ sumsq, int parts,
+    const float *__restrict__ b, const float *__restrict__ alpha, const float *__restrict__ gH_res,
     const float *__restrict__ gH_pre, const float *__restrict__ gH_post, int nC, float eps,
     int sk_iters, int64_t T, BwdTokenBufs o) {
   constexpr int R = Dims<N, MODE>::R, M = Dims<N, MODE>::M;
@@ -142,14 +148,20 @@ __global__ __launch_bounds__(128) void coeffs_bwd_epilogue_kernel(
   float u[M], bb[M], a[R], Hr[N * N], Hp[N], Hq[N], gz[M];
   float gr[N * N], gp[N], gq[N];
   float sums[(MODE == MHCL_RES_SK) ? 2 * kMaxSkIters * N : 1];
+  float ssq = sumsq[t];
 #pragma unroll
   for (int m = 0; m < M; ++m) { u[m] = u_raw[t * M + m]; bb[m] = b[m]; }
+  for (int pt = 1; pt < parts; ++pt) {
+    ssq += sumsq[pt * T + t];
+#pragma unroll
+    for (int m = 0; m < M; ++m) u[m] += u_raw[(pt * T + t) * M + m];
+  }
 #pragma unroll
   for (int e = 0; e < N * N; ++e) gr[e] = gH_res[t * N * N + e];
 #pragma unroll
   for (int j = 0; j < N; ++j) { gp[j] = gH_pre[t * N + j]; gq[j] = gH_post[t * N + j]; }
   const TokenParams p{alpha[0], alpha[1], alpha[2], eps, sk_iters};
-  const float r = token_coeffs<N, MODE>(u, sumsq[t], nC, bb, p, Hr, Hp, Hq, a,
+  const float r = token_coeffs<N, MODE>(u, ssq, nC, bb, p, Hr, Hp, Hq, a,
                                         (MODE == MHCL_RES_SK) ? sums : nullptr);
 #pragma unroll
   for (int e = 0; e < N * N; ++e) o.H_res[t * N * N + e] = Hr[e];
@@ -549,21 +561,22 @@ hipError_t launch_proj_generic(const mhcl_desc &d, int M, const void *x, const f
   });
 }
 
-hipError_t launch_coeffs_epilogue(const mhcl_desc &d, const float *u_raw, const float *sumsq,
-                                  const float *b, const float *alpha, float *H_res, float *H_pre,
+hipError_t launch_coeffs_epilogue(const mhcl_desc &d, int parts, const float *u_raw,
+                                  const float *sumsq, const float *b, const float *alpha, float *H_res, float *H_pre,
                                   float *H_post, hipStream_t s) {
   return dispatch_n(d.n, [&](auto nn) {
     return dispatch_mode(d.res_mode, [&](auto mm) {
       constexpr int N = decltype(nn)::value, MODE = decltype(mm)::value;
       hipLaunchKernelGGL((coeffs_epilogue_kernel<N, MODE>), dim3(blocks_for(d.T, 128)), dim3(128),
-                         0, s, u_raw, sumsq, b, alpha, d.n * d.C, d.eps, d.sk_iters, d.T, H_res,
-                         H_pre, H_post);
+                         0, s, u_raw, sumsq, parts, b, alpha, d.n * d.C, d.eps, d.sk_iters, d.T,
+                         H_res, H_pre, H_post);
       return hipGetLastError();
     });
   });
 }
 
-hipError_t launch_coeffs_bwd_epilogue(const mhcl_desc &d, const float *u_raw, const float *sumsq,
+hipError_t launch_coeffs_bwd_epilogue(const mhcl_desc &d, int parts, const float *u_raw,
+                                      const float *sumsq,
                                       const float *b, const float *alpha, const float *g_H_res,
                                       const float *g_H_pre, const float *g_H_post,
                                       const BwdTokenBufs &o, hipStream_t s) {
@@ -571,8 +584,8 @@ hipError_t launch_coeffs_bwd_epilogue(const mhcl_desc &d, const float *u_raw, co
     return dispatch_mode(d.res_mode, [&](auto mm) {
       constexpr int N = decltype(nn)::value, MODE = decltype(mm)::value;
       hipLaunchKernelGGL((coeffs_bwd_epilogue_kernel<N, MODE>), dim3(blocks_for(d.T, 128)),
-                         dim3(128), 0, s, u_raw, sumsq, b, alpha, g_H_res, g_H_pre, g_H_post,
-                         d.n * d.C, d.eps, d.sk_iters, d.T, o);
+                         dim3(128), 0, s, u_raw, sumsq, parts, b, alpha, g_H_res, g_H_pre,
+                         g_H_post, d.n * d.C, d.eps, d.sk_iters, d.T, o);
       return hipGetLastError();
     });
   });

@@ -38,8 +38,8 @@ struct BwdTokenBufs {
 // ---- generic (plain ALU) kernels: any n in 1..5, bf16 or f32 streams -----
 hipError_t launch_proj_generic(const mhcl_desc &d, int M, const void *x, const float *W,
                                float *u_raw, float *sumsq, hipStream_t s);
-hipError_t launch_coeffs_epilogue(const mhcl_desc &d, const float *u_raw, const float *sumsq,
-                                  const float *b, const float *alpha, float *H_res, float *H_pre,
+hipError_t launch_coeffs_epilogue(const mhcl_desc &d, int parts, const float *u_raw,
+                                  const float *sumsq, const float *b, const float *alpha, float *H_res, float *H_pre,
                                   float *H_post, hipStream_t s);
 hipError_t launch_pre(const mhcl_desc &d, const void *x, const float *H_pre, void *h, hipStream_t s);
 hipError_t launch_post(const mhcl_desc &d, const void *x, const void *y, const float *H_res,
@@ -53,7 +53,8 @@ hipError_t launch_pre_bwd(const mhcl_desc &d, const void *x, const float *H_pre,
 hipError_t launch_bwd_dots(const mhcl_desc &d, const void *x, const void *y, const void *g_xout,
                            const void *g_h, float *g_H_res, float *g_H_post, float *g_H_pre,
                            hipStream_t s);
-hipError_t launch_coeffs_bwd_epilogue(const mhcl_desc &d, const float *u_raw, const float *sumsq,
+hipError_t launch_coeffs_bwd_epilogue(const mhcl_desc &d, int parts, const float *u_raw,
+                                      const float *sumsq,
                                       const float *b, const float *alpha, const float *g_H_res,
                                       const float *g_H_pre, const float *g_H_post,
                                       const BwdTokenBufs &o, hipStream_t s);
@@ -76,6 +77,10 @@ hipError_t launch_param_sums(const mhcl_desc &d, int M, const float *gz, float *
 
 // ---- bf16 fast path (MFMA projections); needs fast_path_ok(desc) ---------
 bool fast_path_ok(const mhcl_desc &d);
+// The MFMA projection may split K over up to kMaxKSplit blocks per token tile;
+// u_raw and sumsq then hold that many slices ([parts][T][M], [parts][T]).
+constexpr int kMaxKSplit = 4;
+int proj_ksplit(const mhcl_desc &d);
 size_t packed_w_b_bytes(const mhcl_desc &d, int M);
 hipError_t launch_pack_w_b(const mhcl_desc &d, int M, const float *W, void *Wp, hipStream_t s);
 hipError_t launch_proj_mfma(const mhcl_desc &d, int M, const void *x, const void *Wp, float *u_raw,
@@ -100,6 +105,9 @@ hipError_t launch_bwd_epilogue_fast(const mhcl_desc &d, const float *b, const fl
                                     const FastBwdWs &w, hipStream_t s);
 hipError_t launch_bwd_out(const mhcl_desc &d, const void *x, const void *g_xout, const void *g_h,
                           const FastBwdWs &w, void *g_x, void *g_y, hipStream_t s);
+hipError_t launch_bwd_out_gw(const mhcl_desc &d, int M, const void *x, const void *g_xout,
+                             const void *g_h, const FastBwdWs &w, void *g_x, void *g_y, float *g_W,
+                             hipStream_t s);
 hipError_t launch_bwd_gw(const mhcl_desc &d, int M, const void *x, const FastBwdWs &w, float *g_W,
                          hipStream_t s);
 hipError_t launch_sum_partials(const float *partials, size_t size, int chunks, float *out,
