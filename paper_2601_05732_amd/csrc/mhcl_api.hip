@@ -334,14 +334,27 @@ int mhcl_bwd_fused(const mhcl_desc *desc, const void *x, const void *y, const fl
   Disarm disarm;
   if (fast_bwd_ok(*desc)) {
     FastBwdWs f(*desc, ws);
+    const bool wide = fast_bwd_wide(*desc);
     MHCL_HIP(launch_pack_w_b(*desc, M, W, f.Wp, s));
     MHCL_HIP(launch_pack_w_a(*desc, M, W, f.Wa, s));
     {
       StageBracket br(MHCL_STAGE_BWD_REDUCE, s);
-      MHCL_HIP(launch_bwd_reduce(*desc, M, x, y, g_xout, g_h, f, s));
+      if (wide) {
+        MHCL_HIP(launch_proj_mfma(*desc, M, x, f.Wp, f.u_raw, f.sumsq, s));
+        MHCL_HIP(launch_bwd_dots(*desc, x, y, g_xout, g_h, f.gH_res, f.gH_post, f.gH_pre, s));
+      } else {
+        MHCL_HIP(launch_bwd_reduce(*desc, M, x, y, g_xout, g_h, f, s));
+      }
     }
     MHCL_HIP(launch_bwd_epilogue_fast(*desc, b, alpha, f, s));
-    {
+    if (wide) {
+      {
+        StageBracket br(MHCL_STAGE_BWD_OUT, s);
+        MHCL_HIP(launch_bwd_out_wide(*desc, M, x, g_xout, g_h, f, g_x, g_y, s));
+      }
+      StageBracket br(MHCL_STAGE_BWD_GW, s);
+      MHCL_HIP(launch_bwd_gw(*desc, M, x, f, g_W, s));
+    } else {
       StageBracket br(MHCL_STAGE_BWD_OUT, s);
       MHCL_HIP(launch_bwd_out_gw(*desc, M, x, g_xout, g_h, f, g_x, g_y, g_W, s));
     }

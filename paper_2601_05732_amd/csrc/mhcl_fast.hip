@@ -425,8 +425,8 @@ __global__ __launch_bounds__(256, 2) void bwd_reduce_kernel(
 // Tokens T..Tpad-1 get zero vr so that padded tiles add nothing to g_W.
 template <int N, int MODE>
 __global__ __launch_bounds__(128) void bwd_epilogue_fast_kernel(
-    const float *__restrict__ u_raw, const float *__restrict__ sumsq, const float *__restrict__ b,
-    const float *__restrict__ alpha, const float *__restrict__ gH_res,
+    const float *__restrict__ u_raw, const float *__restrict__ sumsq, int parts,
+    const float *__restrict__ b, const float *__restrict__ alpha, const float *__restrict__ gH_res,
     const float *__restrict__ gH_pre, const float *__restrict__ gH_post, int nC, float eps,
     int sk_iters, int64_t T, int64_t Tpad, int CP, int MP32, int MP16, float *__restrict__ cpk,
     uint16_t *__restrict__ vr_hi, uint16_t *__restrict__ vr_lo, uint16_t *__restrict__ vrT_hi,
@@ -447,14 +447,20 @@ __global__ __launch_bounds__(128) void bwd_epilogue_fast_kernel(
   float u[M], bb[M], a[R], Hr[N * N], Hp[N], Hq[N], gz[M];
   float gr[N * N], gp[N], gq[N];
   float sums[(MODE == MHCL_RES_SK) ? 2 * kMaxSkIters * N : 1];
+  float ssq = sumsq[t];
 #pragma unroll
   for (int m = 0; m < M; ++m) { u[m] = u_raw[t * M + m]; bb[m] = b[m]; }
+  for (int pt = 1; pt < parts; ++pt) {   // K-split slices of the projection, added in order
+    ssq += sumsq[pt * T + t];
+#pragma unroll
+    for (int m = 0; m < M; ++m) u[m] += u_raw[(pt * T + t) * M + m];
+  }
 #pragma unroll
   for (int e = 0; e < N * N; ++e) gr[e] = gH_res[t * N * N + e];
 #pragma unroll
   for (int j = 0; j < N; ++j) { gp[j] = gH_pre[t * N + j]; gq[j] = gH_post[t * N + j]; }
   const TokenParams p{alpha[0], alpha[1], alpha[2], eps, sk_iters};
-  const float r = token_coeffs<N, MODE>(u, sumsq[t], nC, bb, p, Hr, Hp, Hq, a,
+  const float r = token_coeffs<N, MODE>(u, ssq, nC, bb, p, Hr, Hp, Hq, a,
                                         (MODE == MHCL_RES_SK) ? sums : nullptr);
   float *cp = cpk + t * CP;
 #pragma unroll
@@ -489,162 +495,19 @@ __global__ __launch_bounds__(128) void bwd_epilogue_fast_kernel(
 }
 
 // ---------------------------------------------------------------------------
-// Backward pass 2a: the stream outputs.
+// Backward pass 2 (n <= 4): the stream outputs AND g_W from one read of x.
 //   g_x[j] = sum_i H_res[i][j] g_xout[i] + H_pre[j] g_h + (W vr)[j] - x[j] coefx
 //   g_y    = sum_i H_post[i] g_xout[i]
 // summed in fp32 and rounded to bf16 once.  A block owns one 64-column step of C
 // (all n streams) and a chunk of tokens; its slice of W (A layout, hi + lo)
-// sits in LDS for the whole walk and its waves take the chunk's 16-token
-// groups in turn.  A lane owns 2 x 8 columns of its token (columns 32 u + 8 q
-// + 0..7, u = 0, 1: four lanes read and write whole 128-byte lines in two back
-// to back accesses).  (W vr) comes out of the MFMAs already in that ownership:
-// lane (token, q), quarter h = 2 u + hh gets rows 32 u + 8 q + 4 hh + 0..3.
-template <int N>
-__global__ __launch_bounds__(256, 2) void bwd_out_kernel(
-    const uint16_t *__restrict__ x, const uint16_t *__restrict__ g,
-    const uint16_t *__restrict__ gh, const u32x4 *__restrict__ Wa, const float *__restrict__ cpk,
-    const uint16_t *__restrict__ vr_hi, const uint16_t *__restrict__ vr_lo, int C, int64_t T,
-    int tokens_per_block, int CP, uint16_t *__restrict__ g_x, uint16_t *__restrict__ g_y) {
-  constexpr int NCP = N * N + 2 * N + 1;      // coefficients of one token
-  constexpr int NCP4 = (NCP + 3) / 4;
-  constexpr int kSliceVec = N * 4 * 2 * 64;   // 16-byte words of W per 64-column step
-  extern __shared__ u32x4 lds[];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int r = lane & 15, q = lane >> 4;
-  const int S = blockIdx.x;                    // 64-column step of this block
-  const int c0 = S * 64 + q * 8;
-  const int nS = C / 64;
-  for (int e = threadIdx.x; e < kSliceVec; e += 256) {
-    const int j = e / 512, rem = e % 512;      // 512 words per (stream, step): 4 quarters x hi/lo
-    lds[e] = Wa[static_cast<size_t>(j * nS + S) * 512 + rem];
-  }
-  __syncthreads();
-  const u32x4 *wl = lds + lane;
-
-  const int64_t tb = static_cast<int64_t>(blockIdx.y) * tokens_per_block;
-  int64_t te = tb + tokens_per_block;
-  if (te > T) te = T;
-
-  auto unpack = [](const u32x4 &v, float (&o)[8]) {
-    o[0] = bf16lo(v.x); o[1] = bf16hi(v.x); o[2] = bf16lo(v.y); o[3] = bf16hi(v.y);
-    o[4] = bf16lo(v.z); o[5] = bf16hi(v.z); o[6] = bf16lo(v.w); o[7] = bf16hi(v.w);
-  };
-  auto pack = [](const float (&o)[8]) {
-    u32x4 v;
-    v.x = cvt_pk_bf16(o[0], o[1]); v.y = cvt_pk_bf16(o[2], o[3]);
-    v.z = cvt_pk_bf16(o[4], o[5]); v.w = cvt_pk_bf16(o[6], o[7]);
-    return v;
-  };
-
-  struct In {
-    u32x4 X[N][2], G[N][2], H[2], vbh, vbl;
-    float4 cp[NCP4];
-  };
-  auto load = [&](In &in, int64_t t0) {
-    int64_t tl = t0 + r;
-    if (tl > te - 1) tl = te - 1;
-#pragma unroll
-    for (int j = 0; j < N; ++j)
-#pragma unroll
-      for (int u = 0; u < 2; ++u) {
-        in.X[j][u] = *reinterpret_cast<const u32x4 *>(x + (tl * N + j) * C + c0 + u * 32);
-        in.G[j][u] = *reinterpret_cast<const u32x4 *>(g + (tl * N + j) * C + c0 + u * 32);
-      }
-#pragma unroll
-    for (int u = 0; u < 2; ++u)
-      in.H[u] = *reinterpret_cast<const u32x4 *>(gh + tl * C + c0 + u * 32);
-    in.vbh = *reinterpret_cast<const u32x4 *>(vr_hi + tl * 32 + q * 8);
-    in.vbl = *reinterpret_cast<const u32x4 *>(vr_lo + tl * 32 + q * 8);
-    const float4 *cpp = reinterpret_cast<const float4 *>(cpk + tl * CP);
-#pragma unroll
-    for (int e = 0; e < NCP4; ++e) in.cp[e] = cpp[e];
-  };
-  auto process = [&](const In &in, int64_t t0) {
-    const int64_t t = t0 + r;
-    const bool live = t < te;
-    float cp[NCP4 * 4];
-#pragma unroll
-    for (int e = 0; e < NCP4; ++e) {
-      cp[4 * e] = in.cp[e].x; cp[4 * e + 1] = in.cp[e].y;
-      cp[4 * e + 2] = in.cp[e].z; cp[4 * e + 3] = in.cp[e].w;
-    }
-    const float cx = cp[N * N + 2 * N];
-    // both 8-column halves of a row are produced first and stored back to back,
-    // so that every visit writes whole 128-byte lines
-    float gv[2][N][8], hv[2][8];
-#pragma unroll
-    for (int u = 0; u < 2; ++u) {
-#pragma unroll
-      for (int i = 0; i < N; ++i) unpack(in.G[i][u], gv[u][i]);
-      unpack(in.H[u], hv[u]);
-    }
-    {   // g_y
-      u32x4 ov[2];
-#pragma unroll
-      for (int u = 0; u < 2; ++u) {
-        float o[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          float sacc = 0.f;
-#pragma unroll
-          for (int i = 0; i < N; ++i) sacc += cp[N * N + N + i] * gv[u][i][e];
-          o[e] = sacc;
-        }
-        ov[u] = pack(o);
-      }
-      if (live) {
-        *reinterpret_cast<u32x4 *>(g_y + t * C + c0) = ov[0];
-        *reinterpret_cast<u32x4 *>(g_y + t * C + c0 + 32) = ov[1];
-      }
-    }
-#pragma unroll
-    for (int j = 0; j < N; ++j) {
-      u32x4 ov[2];
-#pragma unroll
-      for (int u = 0; u < 2; ++u) {
-        f32x4 wv[2];
-#pragma unroll
-        for (int hh = 0; hh < 2; ++hh) {
-          const int h = 2 * u + hh;
-          const u32x4 wh = wl[((j * 4 + h) * 2 + 0) * 64], wlo = wl[((j * 4 + h) * 2 + 1) * 64];
-          wv[hh] = mfma16(wh, in.vbh, f32x4{0.f, 0.f, 0.f, 0.f});
-          wv[hh] = mfma16(wlo, in.vbh, wv[hh]);
-          wv[hh] = mfma16(wh, in.vbl, wv[hh]);
-        }
-        float xv[8], o[8];
-        unpack(in.X[j][u], xv);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          float sacc = wv[e >> 2][e & 3] - xv[e] * cx;
-#pragma unroll
-          for (int i = 0; i < N; ++i) sacc += cp[i * N + j] * gv[u][i][e];
-          sacc += cp[N * N + j] * hv[u][e];
-          o[e] = sacc;
-        }
-        ov[u] = pack(o);
-      }
-      if (live) {
-        *reinterpret_cast<u32x4 *>(g_x + (t * N + j) * C + c0) = ov[0];
-        *reinterpret_cast<u32x4 *>(g_x + (t * N + j) * C + c0 + 32) = ov[1];
-      }
-      __builtin_amdgcn_sched_barrier(0);   // one stream's operands and results at a time
-    }
-  };
-
-  // One 16-token group at a time per wave; the other resident waves keep HBM busy.
-  In in;
-  for (int64_t t0 = tb + wave * 16; t0 < te; t0 += 64) {
-    load(in, t0);
-    __builtin_amdgcn_sched_barrier(0);
-    process(in, t0);
-  }
-}
-
-// ---------------------------------------------------------------------------
-// Backward pass 2, fused: bwd_out_kernel's outputs AND g_W from the same read of
-// x (n <= 4, one wave per stream).  Per block iteration the four waves load the
-// tiles of 4 x 16 tokens as above, publish their x tiles in LDS, and wave w
-// then accumulates g_W rows of stream w for all 64 tokens:
+// sits in LDS for the whole walk.  A lane owns 2 x 8 columns of its token
+// (columns 32 u + 8 q + 0..7, u = 0, 1: four lanes read and write whole
+// 128-byte lines in two back to back accesses).  (W vr) comes out of the MFMAs
+// already in that ownership: lane (token, q), quarter h = 2 u + hh gets rows
+// 32 u + 8 q + 4 hh + 0..3.
+// Per block iteration the four waves load the tiles of 4 x 16 tokens, publish
+// their x tiles in LDS, and wave w (one wave per stream) then accumulates the
+// g_W rows of stream w for all 64 tokens:
 //   D[m][k] += vrT[m][token] * x^T[token][k]
 // with x^T obtained by an MFMA against a 0/1 selection matrix (exact) as in
 // bwd_gw_kernel.  Accumulators stay in registers over the block's token chunk;
@@ -885,6 +748,123 @@ __global__ __launch_bounds__(256, 2) void bwd_out_gw_kernel(
 }
 
 // ---------------------------------------------------------------------------
+// Wide case (more than 32 logits, n = 5): the W slice of a 64-column step no
+// longer fits on chip next to the stream tiles, so pass 2 is split in two.
+// First D[t][k] = (W vr_t)[k] as a plain MFMA product with the W rows of one
+// 64-row step resident in LDS (A layout, MS logit steps, hi + lo) and the
+// per-token vectors vr as B operands; D is fp32 [T, nC] in the workspace.
+template <int MS>
+__global__ __launch_bounds__(256, 2) void wv_kernel(const u32x4 *__restrict__ Wa,
+                                                    const uint16_t *__restrict__ vr_hi,
+                                                    const uint16_t *__restrict__ vr_lo, int MP32,
+                                                    int K, int64_t T, int tokens_per_block,
+                                                    float *__restrict__ D) {
+  constexpr int kSliceVec = 4 * MS * 2 * 64;
+  extern __shared__ u32x4 lds[];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int r = lane & 15, q = lane >> 4;
+  const int S = blockIdx.x;
+  for (int e = threadIdx.x; e < kSliceVec; e += 256) lds[e] = Wa[static_cast<size_t>(S) * kSliceVec + e];
+  __syncthreads();
+  const u32x4 *wl = lds + lane;
+  const int64_t tb = static_cast<int64_t>(blockIdx.y) * tokens_per_block;
+  int64_t te = tb + tokens_per_block;
+  if (te > T) te = T;
+  for (int64_t t0 = tb + wave * 16; t0 < te; t0 += 64) {
+    const int64_t t = t0 + r;
+    const bool live = t < te;
+    const int64_t tl = live ? t : te - 1;
+    u32x4 vbh[MS], vbl[MS];
+#pragma unroll
+    for (int ms = 0; ms < MS; ++ms) {
+      vbh[ms] = *reinterpret_cast<const u32x4 *>(vr_hi + tl * MP32 + ms * 32 + q * 8);
+      vbl[ms] = *reinterpret_cast<const u32x4 *>(vr_lo + tl * MP32 + ms * 32 + q * 8);
+    }
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      f32x4 acc[2];
+#pragma unroll
+      for (int hh = 0; hh < 2; ++hh) {
+        const int h = 2 * u + hh;
+        acc[hh] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ms = 0; ms < MS; ++ms) {
+          const u32x4 wh = wl[((h * MS + ms) * 2 + 0) * 64], wlo = wl[((h * MS + ms) * 2 + 1) * 64];
+          acc[hh] = mfma16(wh, vbh[ms], acc[hh]);
+          acc[hh] = mfma16(wlo, vbh[ms], acc[hh]);
+          acc[hh] = mfma16(wh, vbl[ms], acc[hh]);
+        }
+      }
+      if (live) {   // rows 64 S + 32 u + 8 q + 0..7 of token t
+        float4 *dst = reinterpret_cast<float4 *>(D + t * K + 64 * S + 32 * u + 8 * q);
+        dst[0] = make_float4(acc[0][0], acc[0][1], acc[0][2], acc[0][3]);
+        dst[1] = make_float4(acc[1][0], acc[1][1], acc[1][2], acc[1][3]);
+      }
+    }
+  }
+}
+
+// Then the stream outputs in row order (one thread per 8 columns of a token):
+//   g_x[j] = sum_i H_res[i][j] g_xout[i] + H_pre[j] g_h + D[j] - x[j] coefx
+//   g_y    = sum_i H_post[i] g_xout[i]
+template <int N>
+__global__ __launch_bounds__(256) void mix_wide_kernel(
+    const uint16_t *__restrict__ x, const uint16_t *__restrict__ g,
+    const uint16_t *__restrict__ gh, const float *__restrict__ D, const float *__restrict__ cpk,
+    int CP, int C, int64_t T, uint16_t *__restrict__ g_x, uint16_t *__restrict__ g_y) {
+  const int vpr = C / 8;
+  const int64_t idx = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+  if (idx >= T * vpr) return;
+  const int64_t t = idx / vpr;
+  const int c = static_cast<int>(idx % vpr) * 8;
+  const float *cp = cpk + t * CP;
+  auto unpack = [](const u32x4 &v, float (&o)[8]) {
+    o[0] = bf16lo(v.x); o[1] = bf16hi(v.x); o[2] = bf16lo(v.y); o[3] = bf16hi(v.y);
+    o[4] = bf16lo(v.z); o[5] = bf16hi(v.z); o[6] = bf16lo(v.w); o[7] = bf16hi(v.w);
+  };
+  auto pack = [](const float (&o)[8]) {
+    u32x4 v;
+    v.x = cvt_pk_bf16(o[0], o[1]); v.y = cvt_pk_bf16(o[2], o[3]);
+    v.z = cvt_pk_bf16(o[4], o[5]); v.w = cvt_pk_bf16(o[6], o[7]);
+    return v;
+  };
+  float gv[N][8], hv[8];
+#pragma unroll
+  for (int i = 0; i < N; ++i)
+    unpack(*reinterpret_cast<const u32x4 *>(g + (t * N + i) * C + c), gv[i]);
+  unpack(*reinterpret_cast<const u32x4 *>(gh + t * C + c), hv);
+  {
+    float o[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      float sacc = 0.f;
+#pragma unroll
+      for (int i = 0; i < N; ++i) sacc += cp[N * N + N + i] * gv[i][e];
+      o[e] = sacc;
+    }
+    *reinterpret_cast<u32x4 *>(g_y + t * C + c) = pack(o);
+  }
+  const float cx = cp[N * N + 2 * N];
+#pragma unroll
+  for (int j = 0; j < N; ++j) {
+    float xv[8], o[8];
+    unpack(*reinterpret_cast<const u32x4 *>(x + (t * N + j) * C + c), xv);
+    const float4 d0 = *reinterpret_cast<const float4 *>(D + (t * N + j) * C + c);
+    const float4 d1 = *reinterpret_cast<const float4 *>(D + (t * N + j) * C + c + 4);
+    const float dv[8] = {d0.x, d0.y, d0.z, d0.w, d1.x, d1.y, d1.z, d1.w};
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      float sacc = dv[e] - xv[e] * cx;
+#pragma unroll
+      for (int i = 0; i < N; ++i) sacc += cp[i * N + j] * gv[i][e];
+      sacc += cp[N * N + j] * hv[e];
+      o[e] = sacc;
+    }
+    *reinterpret_cast<u32x4 *>(g_x + (t * N + j) * C + c) = pack(o);
+  }
+}
+
+// ---------------------------------------------------------------------------
 // Backward pass 2b: g_W[k][m] = sum_t x_hat[t][k] vr[t][m], the one reduction
 // over tokens.  A wave owns CSW K steps (32 rows of g_W each) and walks a chunk
 // of tokens 32 at a time.  x arrives with tokens across lanes, but the
@@ -1072,10 +1052,19 @@ hipError_t launch_proj_mfma(const mhcl_desc &d, int M, const void *x, const void
 
 
 // ---- fused backward, bf16, n <= 4 -------------------------------------------
-bool fast_bwd_ok(const mhcl_desc &d) { return fast_path_ok(d) && d.n <= 4; }
+// n <= 4 (at most 32 logits): fused passes; n = 5: the wide variant of pass 2
+bool fast_bwd_ok(const mhcl_desc &d) { return fast_path_ok(d); }
+bool fast_bwd_wide(const mhcl_desc &d) { return d.n > 4; }
 
 namespace {
-int gw_xblocks(const mhcl_desc &d) { return (d.n * d.C / 32 + 15) / 16; }   // 4 waves x 4 K steps
+// K steps per wave of bwd_gw_kernel: bounded by its accumulators (2 * NT * 4 registers per step)
+int gw_csw(const mhcl_desc &d) {
+  return logit_tiles(res_logits(d.n, d.res_mode) + 2 * d.n) <= 3 ? 4 : 1;
+}
+int gw_xblocks(const mhcl_desc &d) {
+  const int per_block = 4 * gw_csw(d);
+  return (d.n * d.C / 32 + per_block - 1) / per_block;
+}
 }  // namespace
 
 int out_gw_tokens_per_block(const mhcl_desc &d) {
@@ -1098,11 +1087,12 @@ FastBwdWs::FastBwdWs(const mhcl_desc &d, void *ws) {
   WsCursor c(ws);
   const size_t T = static_cast<size_t>(d.T), Tpad = (T + 63) / 64 * 64;
   const int n = d.n, M = res_logits(d.n, d.res_mode) + 2 * d.n, K = d.n * d.C;
-  CP = 32;
+  CP = n <= 4 ? 32 : 40;
   MP32 = logit_steps(M) * 32;
   MP16 = logit_tiles(M) * 16;
-  u_raw = c.take<float>(T * M);
-  sumsq = c.take<float>(T);
+  parts = fast_bwd_wide(d) ? proj_ksplit(d) : 1;   // the wide path recomputes with proj_mfma_kernel
+  u_raw = c.take<float>(static_cast<size_t>(parts) * T * M);
+  sumsq = c.take<float>(static_cast<size_t>(parts) * T);
   gH_res = c.take<float>(T * n * n);
   gH_pre = c.take<float>(T * n);
   gH_post = c.take<float>(T * n);
@@ -1121,6 +1111,7 @@ FastBwdWs::FastBwdWs(const mhcl_desc &d, void *ws) {
     partials = c.take<float>(chunks * K * M);
   }
   psum = c.take<float>(static_cast<size_t>(param_sum_blocks(d)) * (M + 3));
+  D = fast_bwd_wide(d) ? c.take<float>(T * K) : nullptr;
   bytes = c.off;
 }
 
@@ -1166,7 +1157,7 @@ hipError_t launch_bwd_epilogue_fast(const mhcl_desc &d, const float *b, const fl
     constexpr int N = decltype(nn)::value, MODE = decltype(mm)::value;
     hipLaunchKernelGGL((bwd_epilogue_fast_kernel<N, MODE>),
                        dim3(static_cast<unsigned>((Tpad + 127) / 128)), dim3(128), 0, s, w.u_raw,
-                       w.sumsq, b, alpha, w.gH_res, w.gH_pre, w.gH_post, d.n * d.C, d.eps,
+                       w.sumsq, w.parts, b, alpha, w.gH_res, w.gH_pre, w.gH_post, d.n * d.C, d.eps,
                        d.sk_iters, d.T, Tpad, w.CP, w.MP32, w.MP16, w.cpk, w.vr_hi, w.vr_lo,
                        w.vrT_hi, w.vrT_lo, w.gz);
     return hipGetLastError();
@@ -1179,29 +1170,7 @@ hipError_t launch_bwd_epilogue_fast(const mhcl_desc &d, const float *b, const fl
     case 2: return lite ? go(std::integral_constant<int, 2>{}, L{}) : go(std::integral_constant<int, 2>{}, S{});
     case 3: return lite ? go(std::integral_constant<int, 3>{}, L{}) : go(std::integral_constant<int, 3>{}, S{});
     case 4: return lite ? go(std::integral_constant<int, 4>{}, L{}) : go(std::integral_constant<int, 4>{}, S{});
-  }
-  return hipErrorInvalidValue;
-}
-
-hipError_t launch_bwd_out(const mhcl_desc &d, const void *x, const void *g_xout, const void *g_h,
-                          const FastBwdWs &w, void *g_x, void *g_y, hipStream_t s) {
-  constexpr int kTokensPerBlock = 512;
-  auto go = [&](auto nn) {
-    constexpr int N = decltype(nn)::value;
-    const dim3 grid(d.C / 64, static_cast<unsigned>((d.T + kTokensPerBlock - 1) / kTokensPerBlock));
-    hipLaunchKernelGGL(bwd_out_kernel<N>, grid, dim3(256), N * 4 * 2 * 64 * 16, s,
-                       static_cast<const uint16_t *>(x),
-                       static_cast<const uint16_t *>(g_xout), static_cast<const uint16_t *>(g_h),
-                       reinterpret_cast<const u32x4 *>(w.Wa), w.cpk, w.vr_hi, w.vr_lo, d.C, d.T,
-                       kTokensPerBlock, w.CP, static_cast<uint16_t *>(g_x),
-                       static_cast<uint16_t *>(g_y));
-    return hipGetLastError();
-  };
-  switch (d.n) {
-    case 1: return go(std::integral_constant<int, 1>{});
-    case 2: return go(std::integral_constant<int, 2>{});
-    case 3: return go(std::integral_constant<int, 3>{});
-    case 4: return go(std::integral_constant<int, 4>{});
+    case 5: return lite ? go(std::integral_constant<int, 5>{}, L{}) : go(std::integral_constant<int, 5>{}, S{});
   }
   return hipErrorInvalidValue;
 }
@@ -1215,19 +1184,45 @@ hipError_t launch_bwd_gw(const mhcl_desc &d, int M, const void *x, const FastBwd
   float *dst = chunks == 1 ? g_W : w.partials;
   hipError_t e = dispatch_nt(logit_tiles(M), [&](auto nt) {
     constexpr int NT = decltype(nt)::value;
-    if constexpr (NT <= 3) {
-      hipLaunchKernelGGL((bwd_gw_kernel<NT, 4>), dim3(gw_xblocks(d), chunks), dim3(256), 0, s,
-                         static_cast<const uint16_t *>(x), w.vrT_hi, w.vrT_lo, K, M, w.MP16, d.T,
-                         nblk, bpc, dst);
-      return hipGetLastError();
-    } else {
-      return hipErrorInvalidValue;
-    }
+    constexpr int CSW = NT <= 3 ? 4 : 1;
+    hipLaunchKernelGGL((bwd_gw_kernel<NT, CSW>), dim3(gw_xblocks(d), chunks), dim3(256), 0, s,
+                       static_cast<const uint16_t *>(x), w.vrT_hi, w.vrT_lo, K, M, w.MP16, d.T,
+                       nblk, bpc, dst);
+    return hipGetLastError();
   });
   if (e != hipSuccess || chunks == 1) return e;
   return launch_sum_partials(w.partials, static_cast<size_t>(K) * M, chunks, g_W, s);
 }
 
+// wide pass 2: D = W vr, then g_x and g_y
+hipError_t launch_bwd_out_wide(const mhcl_desc &d, int M, const void *x, const void *g_xout,
+                               const void *g_h, const FastBwdWs &w, void *g_x, void *g_y,
+                               hipStream_t s) {
+  const int K = d.n * d.C, MS = logit_steps(M);
+  constexpr int kTokensPerBlock = 1024;
+  const dim3 grid(K / 64, static_cast<unsigned>((d.T + kTokensPerBlock - 1) / kTokensPerBlock));
+  auto wv = [&](auto ms) {
+    constexpr int kMS = decltype(ms)::value;
+    hipLaunchKernelGGL(wv_kernel<kMS>, grid, dim3(256), 4 * kMS * 2 * 64 * 16, s,
+                       reinterpret_cast<const u32x4 *>(w.Wa), w.vr_hi, w.vr_lo, w.MP32, K, d.T,
+                       kTokensPerBlock, w.D);
+    return hipGetLastError();
+  };
+  hipError_t e = hipErrorInvalidValue;
+  switch (MS) {
+    case 1: e = wv(std::integral_constant<int, 1>{}); break;
+    case 2: e = wv(std::integral_constant<int, 2>{}); break;
+    case 5: e = wv(std::integral_constant<int, 5>{}); break;
+  }
+  if (e != hipSuccess) return e;
+  if (d.n != 5) return hipErrorInvalidValue;
+  const int64_t vecs = d.T * (d.C / 8);
+  hipLaunchKernelGGL(mix_wide_kernel<5>, dim3(static_cast<unsigned>((vecs + 255) / 256)), dim3(256),
+                     0, s, static_cast<const uint16_t *>(x), static_cast<const uint16_t *>(g_xout),
+                     static_cast<const uint16_t *>(g_h), w.D, w.cpk, w.CP, d.C, d.T,
+                     static_cast<uint16_t *>(g_x), static_cast<uint16_t *>(g_y));
+  return hipGetLastError();
+}
 
 // g_x, g_y and g_W from one pass (n <= 4)
 hipError_t launch_bwd_out_gw(const mhcl_desc &d, int M, const void *x, const void *g_xout,

@@ -88,12 +88,13 @@ hipError_t launch_proj_mfma(const mhcl_desc &d, int M, const void *x, const void
 
 // fused backward on the fast path (needs fast_bwd_ok(desc))
 bool fast_bwd_ok(const mhcl_desc &d);
+bool fast_bwd_wide(const mhcl_desc &d);   // n = 5: pass 2 split into W vr and the mixing
 int gw_chunks_fast(const mhcl_desc &d);
 struct FastBwdWs {
-  float *u_raw, *sumsq, *gH_res, *gH_pre, *gH_post, *cpk, *gz, *partials, *psum;
+  float *u_raw, *sumsq, *gH_res, *gH_pre, *gH_post, *cpk, *gz, *partials, *psum, *D;
   uint16_t *vr_hi, *vr_lo, *vrT_hi, *vrT_lo;
   char *Wp, *Wa;
-  int CP, MP32, MP16;
+  int CP, MP32, MP16, parts;
   size_t bytes;
   FastBwdWs(const mhcl_desc &d, void *ws);
 };
@@ -103,8 +104,9 @@ hipError_t launch_bwd_reduce(const mhcl_desc &d, int M, const void *x, const voi
                              hipStream_t s);
 hipError_t launch_bwd_epilogue_fast(const mhcl_desc &d, const float *b, const float *alpha,
                                     const FastBwdWs &w, hipStream_t s);
-hipError_t launch_bwd_out(const mhcl_desc &d, const void *x, const void *g_xout, const void *g_h,
-                          const FastBwdWs &w, void *g_x, void *g_y, hipStream_t s);
+hipError_t launch_bwd_out_wide(const mhcl_desc &d, int M, const void *x, const void *g_xout,
+                               const void *g_h, const FastBwdWs &w, void *g_x, void *g_y,
+                               hipStream_t s);
 hipError_t launch_bwd_out_gw(const mhcl_desc &d, int M, const void *x, const void *g_xout,
                              const void *g_h, const FastBwdWs &w, void *g_x, void *g_y, float *g_W,
                              hipStream_t s);
