@@ -179,3 +179,60 @@ def test_stream_sum_conservation_full_width():
     rhs = inp["x"].double().sum(dim=1) + L.H_post.double().sum(dim=1, keepdim=True) * inp["y"].double()
     # each of the n outputs is rounded to bf16 once: |err| <= n * 2^-9 * max|x_out|
     assert float((lhs - rhs).abs().max()) <= 4 * 2.0 ** -9 * float(L.x_out.abs().max())
+
+
+def test_one_hot_weights_give_exact_permutation_matrices():
+    # b_res = 0 at one permutation and -1e4 elsewhere, W = 0: H_res must be that
+    # permutation matrix exactly (Theorem 3.1, vertices of the Birkhoff polytope)
+    import itertools
+    wl = _small("onehot", n=4, C=64, T=24)
+    inp = si.make_inputs(wl, seed=2, device="cuda")
+    inp["W"].zero_()
+    perms = list(itertools.permutations(range(4)))
+    L = GpuLayer(desc_for(wl), inp)
+    for k in (0, 5, 17, 23):
+        b = torch.zeros(32, device="cuda")
+        b[:24] = -1e4
+        b[k] = 0.0
+        inp["b"] = b
+        L.forward_fused()
+        torch.cuda.synchronize()
+        expect = torch.zeros(4, 4)
+        for i, j in enumerate(perms[k]):
+            expect[i, j] = 1.0
+        assert torch.equal(L.H_res.cpu(), expect.expand(24, 4, 4)), k
+        # x_out[i] = x[sigma_k(i)] + H_post[i] y: the residual part is a pure stream permutation
+        ref = oracle_reference(inp, wl, backward=False)
+        assert rel_err(to_np64(L.x_out), ref["x_out"]) <= TOL_BF16_OUT
+
+
+def test_eps_zero_and_large_width():
+    # eps = 0 (pure RMS) on non-zero input; C = 8192 exercises long rows (n*C = 16384 per token)
+    wl = si.Workload("eps0", n=2, C=8192, T=100, io="bf16", eps=0.0)
+    inp = si.make_inputs(wl, seed=5, device="cuda")
+    ref = oracle_reference(inp, wl)
+    L = GpuLayer(desc_for(wl), inp)
+    L.step()
+    torch.cuda.synchronize()
+    _check_forward(L, ref, wl)
+    _check_backward(L, ref, wl)
+
+
+def test_saturated_gates_stay_finite():
+    # very large |bias| on the gate logits: sigmoid saturates to 0 / 1 (2 for H_post) without NaN
+    wl = _small("saturated", C=64, T=16)
+    inp = si.make_inputs(wl, seed=6, device="cuda")
+    b = inp["b"].clone()
+    b[24:28] = torch.tensor([80.0, -80.0, 30.0, -30.0], device="cuda")
+    b[28:32] = torch.tensor([-80.0, 80.0, -30.0, 30.0], device="cuda")
+    inp["b"] = b
+    ref = oracle_reference(inp, wl)
+    L = GpuLayer(desc_for(wl), inp)
+    L.step()
+    torch.cuda.synchronize()
+    for t in (L.H_pre, L.H_post, L.g_x.float(), L.g_W, L.g_b):
+        assert torch.isfinite(t).all()
+    _check_forward(L, ref, wl)
+    _check_backward(L, ref, wl, params=False)
+    for name in ("g_W", "g_b", "g_alpha"):
+        assert rel_err(to_np64(getattr(L, name)), ref[name]) <= TOL_BF16_PARAM, name
