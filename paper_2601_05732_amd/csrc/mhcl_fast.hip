@@ -1068,8 +1068,16 @@ int gw_xblocks(const mhcl_desc &d) {
 }  // namespace
 
 int out_gw_tokens_per_block(const mhcl_desc &d) {
-  // at most 16 partial copies of g_W, blocks of a whole number of 64-token iterations
-  int64_t tpb = ((d.T + 15) / 16 + 63) / 64 * 64;
+  // Token chunks: enough of them that (C / 64) x chunks fills the chip about four
+  // times over, at least 16, never more than 64 MiB of partial g_W copies, and
+  // blocks of a whole number of 64-token iterations (at least 512 tokens).
+  const int64_t M = res_logits(d.n, d.res_mode) + 2 * d.n;
+  const int64_t copy_bytes = static_cast<int64_t>(d.n) * d.C * M * 4;
+  int64_t chunks = (1024 + d.C / 64 - 1) / (d.C / 64);
+  if (chunks < 16) chunks = 16;
+  const int64_t cap = (64ll << 20) / copy_bytes;
+  if (chunks > cap) chunks = cap < 1 ? 1 : cap;
+  int64_t tpb = ((d.T + chunks - 1) / chunks + 63) / 64 * 64;
   if (tpb < 512) tpb = 512;
   return static_cast<int>(tpb);
 }
@@ -1199,7 +1207,10 @@ hipError_t launch_bwd_out_wide(const mhcl_desc &d, int M, const void *x, const v
                                const void *g_h, const FastBwdWs &w, void *g_x, void *g_y,
                                hipStream_t s) {
   const int K = d.n * d.C, MS = logit_steps(M);
-  constexpr int kTokensPerBlock = 1024;
+  // 1024 tokens per block, more once that would exceed the grid's second dimension
+  int64_t tpb = 1024;
+  while ((d.T + tpb - 1) / tpb > 32768) tpb *= 2;
+  const int kTokensPerBlock = static_cast<int>(tpb);
   const dim3 grid(K / 64, static_cast<unsigned>((d.T + kTokensPerBlock - 1) / kTokensPerBlock));
   auto wv = [&](auto ms) {
     constexpr int kMS = decltype(ms)::value;
