@@ -135,14 +135,19 @@ __global__ __launch_bounds__(256, 2) void proj_mfma_kernel(const uint16_t *__res
 #pragma unroll
     for (int i = 0; i < WV; ++i) lds[buf * Cfg::kChunkVec + i * 256 + threadIdx.x] = wst[i];
   };
-  auto compute = [&](const u32x4 (&av)[TG][KC], int buf, int c) {
+  // `tail`: the chunk may run past the last K step; such steps get a zero A tile
+  auto compute = [&](const u32x4 (&av)[TG][KC], int buf, int c, auto tail) {
     const u32x4 *wb = lds + buf * Cfg::kChunkVec;
 #pragma unroll
     for (int s = 0; s < KC; ++s) {
-      const bool valid = c * KC + s < nsteps;
       u32x4 at[TG];
 #pragma unroll
-      for (int g = 0; g < TG; ++g) at[g] = valid ? av[g][s] : u32x4{0, 0, 0, 0};
+      for (int g = 0; g < TG; ++g) {
+        if constexpr (decltype(tail)::value)
+          at[g] = c * KC + s < nsteps ? av[g][s] : u32x4{0, 0, 0, 0};
+        else
+          at[g] = av[g][s];
+      }
 #pragma unroll
       for (int j = 0; j < NT; ++j) {
         const u32x4 bh = wb[((s * NT + j) * 2 + 0) * 64 + lane];
@@ -157,6 +162,8 @@ __global__ __launch_bounds__(256, 2) void proj_mfma_kernel(const uint16_t *__res
       for (int g = 0; g < TG; ++g) ss[g] = mfma16(at[g], at[g], ss[g]);
     }
   };
+  constexpr std::false_type kFull{};
+  constexpr std::true_type kTail{};
 
   // W is requested before the A tiles of the same chunk: loads return in order,
   // so staging W into LDS only has to wait for the W loads and leaves the A
@@ -169,24 +176,24 @@ __global__ __launch_bounds__(256, 2) void proj_mfma_kernel(const uint16_t *__res
   for (; c + 2 < nchunks; c += 2) {
     load_w(c + 1); load_a(a[1], c + 1);
     __builtin_amdgcn_sched_barrier(0);   // keep the whole next chunk in flight during compute
-    compute(a[0], 0, c);
+    compute(a[0], 0, c, kFull);
     store_w(1);
     __syncthreads();
     load_w(c + 2); load_a(a[0], c + 2);
     __builtin_amdgcn_sched_barrier(0);
-    compute(a[1], 1, c + 1);
+    compute(a[1], 1, c + 1, kFull);
     store_w(0);
     __syncthreads();
   }
   if (c + 1 < nchunks) {
     load_w(c + 1); load_a(a[1], c + 1);
     __builtin_amdgcn_sched_barrier(0);
-    compute(a[0], 0, c);
+    compute(a[0], 0, c, kFull);
     store_w(1);
     __syncthreads();
-    compute(a[1], 1, c + 1);
+    compute(a[1], 1, c + 1, kTail);
   } else {
-    compute(a[0], 0, c);
+    compute(a[0], 0, c, kTail);
   }
 
   // D layout: lane (r, q) holds logit 16 j + r for tokens 4 q + i
