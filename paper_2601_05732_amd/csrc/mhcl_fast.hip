@@ -990,6 +990,144 @@ __global__ __launch_bounds__(256, 2) void bwd_gw_kernel(
   }
 }
 
+// The same reduction for many logit tiles (n = 5: NT = 9).  Every wave of a block
+// needs the whole vrT block of the 32 tokens at hand (18 KiB), so the block stages
+// it in LDS once (double buffered, requested one iteration ahead) instead of
+// each wave fetching it from L2.
+template <int NT, int CSW>
+__global__ __launch_bounds__(256, 2) void bwd_gw_lds_kernel(
+    const uint16_t *__restrict__ x, const uint16_t *__restrict__ vrT_hi,
+    const uint16_t *__restrict__ vrT_lo, int K, int M, int64_t T, int64_t nblk,
+    int blks_per_chunk, float *__restrict__ out) {
+  constexpr int MP16 = NT * 16;
+  constexpr int kPartVec = MP16 * 4;            // 16-byte words of one part (hi or lo) of a block
+  constexpr int kBufVec = 2 * kPartVec;
+  constexpr int WV = (kBufVec + 255) / 256;
+  __shared__ u32x4 lds[2 * kBufVec];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int r = lane & 15, q = lane >> 4;
+  const int s0 = (blockIdx.x * 4 + wave) * CSW;
+  const int nsteps = K / 32;
+  u32x4 sel[2];
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    uint32_t w[4];
+#pragma unroll
+    for (int e2 = 0; e2 < 4; ++e2) {
+      const int k0 = 8 * q + 2 * e2, k1 = k0 + 1;
+      w[e2] = (k0 == 16 * h + r ? 0x3F80u : 0u) | (k1 == 16 * h + r ? 0x3F800000u : 0u);
+    }
+    sel[h] = u32x4{w[0], w[1], w[2], w[3]};
+  }
+  f32x4 acc[CSW][2][NT];
+#pragma unroll
+  for (int c = 0; c < CSW; ++c)
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+      for (int mt = 0; mt < NT; ++mt) acc[c][h][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  const int64_t b0 = static_cast<int64_t>(blockIdx.y) * blks_per_chunk;
+  int64_t b1 = b0 + blks_per_chunk;
+  if (b1 > nblk) b1 = nblk;
+
+  const u32x4 *vh = reinterpret_cast<const u32x4 *>(vrT_hi);
+  const u32x4 *vl = reinterpret_cast<const u32x4 *>(vrT_lo);
+  u32x4 wst[WV], X[CSW][2];
+  auto load_v = [&](int64_t blk) {
+#pragma unroll
+    for (int i = 0; i < WV; ++i) {
+      int e = i * 256 + threadIdx.x;
+      if (e > kBufVec - 1) e = kBufVec - 1;
+      wst[i] = e < kPartVec ? vh[blk * kPartVec + e] : vl[blk * kPartVec + (e - kPartVec)];
+    }
+  };
+  auto store_v = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < WV; ++i) {
+      int e = i * 256 + threadIdx.x;
+      if (e > kBufVec - 1) e = kBufVec - 1;
+      lds[buf * kBufVec + e] = wst[i];
+    }
+  };
+  auto load_x = [&](u32x4 (&d)[CSW][2], int64_t blk) {
+#pragma unroll
+    for (int gI = 0; gI < 2; ++gI) {
+      int64_t t = blk * 32 + gI * 16 + r;
+      if (t > T - 1) t = T - 1;
+#pragma unroll
+      for (int c = 0; c < CSW; ++c) {
+        const int s = s0 + c < nsteps ? s0 + c : nsteps - 1;
+        d[c][gI] = *reinterpret_cast<const u32x4 *>(x + t * K + s * 32 + q * 8);
+      }
+    }
+  };
+  // nxt: the block whose x rows are requested once this one's are transposed
+  auto process = [&](u32x4 (&xx)[CSW][2], int buf, int64_t nxt) {
+    // lane (logit row r, q) takes tokens 4q..4q+3 and 16+4q..: two 8-byte pieces of its 64-byte row
+    const uint32_t *base = reinterpret_cast<const uint32_t *>(lds + buf * kBufVec);
+    u32x4 bt[CSW][2];
+#pragma unroll
+    for (int c = 0; c < CSW; ++c)
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const f32x4 z = f32x4{0.f, 0.f, 0.f, 0.f};
+        const f32x4 t0 = mfma16(xx[c][0], sel[h], z);
+        const f32x4 t1 = mfma16(xx[c][1], sel[h], z);
+        bt[c][h].x = cvt_pk_bf16(t0[0], t0[1]); bt[c][h].y = cvt_pk_bf16(t0[2], t0[3]);
+        bt[c][h].z = cvt_pk_bf16(t1[0], t1[1]); bt[c][h].w = cvt_pk_bf16(t1[2], t1[3]);
+      }
+    load_x(xx, nxt);
+#pragma unroll
+    for (int mt = 0; mt < NT; ++mt) {
+      const int row = (mt * 16 + r) * 16 + 2 * q;     // in 4-byte words
+      const u32x2 h0 = *reinterpret_cast<const u32x2 *>(base + row);
+      const u32x2 h1 = *reinterpret_cast<const u32x2 *>(base + row + 8);
+      const u32x2 l0 = *reinterpret_cast<const u32x2 *>(base + kPartVec * 4 + row);
+      const u32x2 l1 = *reinterpret_cast<const u32x2 *>(base + kPartVec * 4 + row + 8);
+      const u32x4 ah = u32x4{h0.x, h0.y, h1.x, h1.y}, al = u32x4{l0.x, l0.y, l1.x, l1.y};
+#pragma unroll
+      for (int c = 0; c < CSW; ++c)
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+          acc[c][h][mt] = mfma16(ah, bt[c][h], acc[c][h][mt]);
+          acc[c][h][mt] = mfma16(al, bt[c][h], acc[c][h][mt]);
+        }
+    }
+  };
+
+  if (b0 < b1) {   // uniform over the block; an empty chunk still writes its zeros
+    load_v(b0);
+    load_x(X, b0);
+    for (int64_t blk = b0; blk < b1; ++blk) {
+      const int buf = static_cast<int>(blk - b0) & 1;
+      store_v(buf);
+      __syncthreads();
+      const int64_t nxt = blk + 1 < b1 ? blk + 1 : blk;
+      load_v(nxt);
+      process(X, buf, nxt);
+    }
+  }
+
+  float *dst = out + static_cast<size_t>(blockIdx.y) * K * M;
+#pragma unroll
+  for (int c = 0; c < CSW; ++c) {
+    if (s0 + c < nsteps) {
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const int k = (s0 + c) * 32 + 16 * h + r;
+#pragma unroll
+        for (int mt = 0; mt < NT; ++mt)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const int m = mt * 16 + 4 * q + i;
+            if (m < M) dst[static_cast<size_t>(k) * M + m] = acc[c][h][mt][i];
+          }
+      }
+    }
+  }
+}
+
 template <typename F>
 hipError_t dispatch_nt(int NT, F &&f) {
   switch (NT) {
@@ -1066,7 +1204,7 @@ bool fast_bwd_wide(const mhcl_desc &d) { return d.n > 4; }
 namespace {
 // K steps per wave of bwd_gw_kernel: bounded by its accumulators (2 * NT * 4 registers per step)
 int gw_csw(const mhcl_desc &d) {
-  return logit_tiles(res_logits(d.n, d.res_mode) + 2 * d.n) <= 3 ? 4 : 1;
+  return logit_tiles(res_logits(d.n, d.res_mode) + 2 * d.n) <= 3 ? 4 : 2;
 }
 int gw_xblocks(const mhcl_desc &d) {
   const int per_block = 4 * gw_csw(d);
@@ -1091,7 +1229,9 @@ int out_gw_tokens_per_block(const mhcl_desc &d) {
 
 int gw_chunks_fast(const mhcl_desc &d) {
   const int64_t nblk = (d.T + 31) / 32;
-  int64_t c = (512 + gw_xblocks(d) - 1) / gw_xblocks(d);
+  // two blocks fit a compute unit: the largest chunk count that keeps the grid at
+  // one round of 512 blocks
+  int64_t c = 512 / gw_xblocks(d);
   if (c > 64) c = 64;
   if (c > nblk) c = nblk;
   if (c < 1) c = 1;
@@ -1199,10 +1339,15 @@ hipError_t launch_bwd_gw(const mhcl_desc &d, int M, const void *x, const FastBwd
   float *dst = chunks == 1 ? g_W : w.partials;
   hipError_t e = dispatch_nt(logit_tiles(M), [&](auto nt) {
     constexpr int NT = decltype(nt)::value;
-    constexpr int CSW = NT <= 3 ? 4 : 1;
-    hipLaunchKernelGGL((bwd_gw_kernel<NT, CSW>), dim3(gw_xblocks(d), chunks), dim3(256), 0, s,
-                       static_cast<const uint16_t *>(x), w.vrT_hi, w.vrT_lo, K, M, w.MP16, d.T,
-                       nblk, bpc, dst);
+    if constexpr (NT <= 3) {
+      hipLaunchKernelGGL((bwd_gw_kernel<NT, 4>), dim3(gw_xblocks(d), chunks), dim3(256), 0, s,
+                         static_cast<const uint16_t *>(x), w.vrT_hi, w.vrT_lo, K, M, w.MP16, d.T,
+                         nblk, bpc, dst);
+    } else {
+      hipLaunchKernelGGL((bwd_gw_lds_kernel<NT, 2>), dim3(gw_xblocks(d), chunks), dim3(256), 0, s,
+                         static_cast<const uint16_t *>(x), w.vrT_hi, w.vrT_lo, K, M, d.T, nblk, bpc,
+                         dst);
+    }
     return hipGetLastError();
   });
   if (e != hipSuccess || chunks == 1) return e;

@@ -72,6 +72,7 @@ SMALL_CASES = [
     _small("bf16_n5", n=5, C=96, T=45),
     _small("bf16_n5_sk", n=5, C=64, T=33, res_mode="sk"),
     _small("bf16_n5_c128", n=5, C=128, T=150),                 # 130 logits: nine MFMA logit tiles
+    _small("bf16_n5_empty_chunks", n=5, C=64, T=2230),         # 70 token blocks over 64 g_W chunks: 29 stay empty
     _small("f32_n3", n=3, C=40, T=19, io="f32"),
     _small("bf16_c4096", C=4096, T=70),                        # full width, several tiles + tail
     _small("one_token", C=64, T=1),
