@@ -182,6 +182,32 @@ def relative_range(X):
     return nu
 
 
+def logits(x, W, b, alpha, eps=1e-6, res_mode="lite"):
+    """z [T, M]: all logits, columns [res | pre | post]."""
+    x, W, b, alpha = _f64(x), _f64(W), _f64(b), _f64(alpha)
+    T, n, C = x.shape
+    R = math.factorial(n) if res_mode == "lite" else n * n
+    M = R + 2 * n
+    assert W.shape == (n * C, M) and b.shape == (M,) and alpha.shape == (3,)
+    z = np.empty((T, M))
+    _load().mhclo_logits(*_dims(x), ctypes.c_int(R), _p(x), _p(W), _p(b), _p(alpha),
+                         ctypes.c_double(eps), _p(z))
+    return z
+
+
+def ds_chain(H):
+    """H [L, T, n, n] -> dict of colsum [L,T,n], l1 [L,T], prod [T,n,n],
+    prod_colsum [L,T,n], prod_l1 [L,T]."""
+    H = _f64(H)
+    L, T, n, _ = H.shape
+    out = dict(colsum=np.empty((L, T, n)), l1=np.empty((L, T)), prod=np.empty((T, n, n)),
+               prod_colsum=np.empty((L, T, n)), prod_l1=np.empty((L, T)))
+    _load().mhclo_ds_chain(ctypes.c_int(n), ctypes.c_int(L), ctypes.c_long(T), _p(H),
+                           _p(out["colsum"]), _p(out["l1"]), _p(out["prod"]),
+                           _p(out["prod_colsum"]), _p(out["prod_l1"]))
+    return out
+
+
 def forward(x, W, b, alpha, y, eps=1e-6, res_mode="lite", iters=20):
     """Whole forward of one layer with y = f(h) supplied: coefficients, h, x_out."""
     if res_mode == "lite":

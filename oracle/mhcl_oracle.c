@@ -15,6 +15,8 @@
  *                                         above it; SK as described in Sec. 1
  *                                         and below Eq. (2) (20 repetitions)
  *   stream mixing ........................ Sec. 2, Eq. (1)
+ *   l1 error, relative range ............. Sec. 3.1, footnote 1 and Eq. (3)
+ *   column sums, product over layers ..... Sec. 3.1 last paragraph, Sec. 4.3
  *   backward ............................. not in the paper: chain rule applied
  *                                         to the forward definitions above
  *
@@ -29,7 +31,10 @@
  * invariants, one-hot / uniform / n=1 / n=2 closed forms, the closed form at
  * the paper's initialisation, an independent library implementation of the
  * forward, the paper's 3x3 SK example, central finite differences and a
- * library autograd for every backward.  No function here is unpinned.
+ * library autograd for every backward; for the diagnostics, composition of
+ * permutations, scaled doubly stochastic chains in closed form, a library
+ * matrix product and the printed column sums of the 3x3 example.  No function
+ * here is unpinned.
  *
  * All arrays are dense row-major doubles.  Tokens are independent; loops over
  * tokens are OpenMP-parallel, every sum inside a token and every sum over
@@ -490,5 +495,71 @@ void mhclo_relative_range(int n, long T, const double *X, double *nu)
             if (Xt[e] > 0.0 && Xt[e] < mn) mn = Xt[e];
         }
         nu[t] = mn / mx;
+    }
+}
+
+/* The logits themselves (Sec. 3.2, the three lines above Eq. (4); Sec. 2 for
+ * the Sinkhorn-Knopp form): z = alpha_g (RMSNorm(x_hat) W) + b for every
+ * token, [T][M], R = number of residual logits (n! or n^2). */
+void mhclo_logits(int n, int C, long T, int R, const double *x, const double *W, const double *b,
+                  const double *alpha, double eps, double *z)
+{
+    int nC = n * C, M = R + 2 * n;
+#pragma omp parallel
+    {
+        double *xn = (double *)malloc(sizeof(double) * nC);
+        double *u = (double *)malloc(sizeof(double) * M);
+#pragma omp for schedule(static)
+        for (long t = 0; t < T; ++t) {
+            double r;
+            token_logits(nC, M, R, n, x + (size_t)t * nC, W, b, alpha, eps, xn, &r, u,
+                         z + (size_t)t * M);
+        }
+        free(xn); free(u);
+    }
+}
+
+/* Sec. 3.1 (accumulation over depth) and Sec. 4.3 (column sums of single
+ * residual matrices and of their product over the layers): for L layers of
+ * per-token matrices H[l][t] (n x n) this writes
+ *   colsum[l][t][j]      = sum_i H[l][t][i][j]
+ *   l1[l][t]             = l1 error of H[l][t]           (footnote 1 of Sec. 3.1)
+ *   Q_l = H[l] Q_{l-1}, Q_0 = I   (the matrix that carries x_1 to x_{l+1} when
+ *                                  only the residual term of Eq. (1) is kept)
+ *   prod_colsum[l][t][j] = sum_i Q_l[i][j],   prod_l1[l][t] = l1 error of Q_l
+ *   prod[t]              = Q_L
+ * The paper does not say on which side later layers multiply; this takes the
+ * order in which Eq. (1) applies them. */
+void mhclo_ds_chain(int n, int L, long T, const double *H, double *colsum, double *l1,
+                    double *prod, double *prod_colsum, double *prod_l1)
+{
+    int nn = n * n;
+    for (long t = 0; t < T; ++t) {
+        double Q[MAXN * MAXN], Qn[MAXN * MAXN];
+        for (int i = 0; i < n; ++i)
+            for (int j = 0; j < n; ++j) Q[i * n + j] = (i == j) ? 1.0 : 0.0;
+        for (int l = 0; l < L; ++l) {
+            const double *Hl = H + ((size_t)l * T + t) * nn;
+            for (int j = 0; j < n; ++j) {
+                double s = 0.0;
+                for (int i = 0; i < n; ++i) s += Hl[i * n + j];
+                colsum[((size_t)l * T + t) * n + j] = s;
+            }
+            mhclo_ds_l1_error(n, 1, Hl, l1 + (size_t)l * T + t);
+            for (int i = 0; i < n; ++i)
+                for (int j = 0; j < n; ++j) {
+                    double s = 0.0;
+                    for (int k = 0; k < n; ++k) s += Hl[i * n + k] * Q[k * n + j];
+                    Qn[i * n + j] = s;
+                }
+            memcpy(Q, Qn, sizeof(double) * nn);
+            for (int j = 0; j < n; ++j) {
+                double s = 0.0;
+                for (int i = 0; i < n; ++i) s += Q[i * n + j];
+                prod_colsum[((size_t)l * T + t) * n + j] = s;
+            }
+            mhclo_ds_l1_error(n, 1, Q, prod_l1 + (size_t)l * T + t);
+        }
+        memcpy(prod + (size_t)t * nn, Q, sizeof(double) * nn);
     }
 }

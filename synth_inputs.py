@@ -62,6 +62,12 @@ WORKLOADS = {
     "n3_c1024": Workload("n3_c1024", n=3, C=1024, T=65536),
     "n5_c2560": Workload("n5_c2560", n=5, C=2560, T=16384),
     "n4_c4096_sk": Workload("n4_c4096_sk", n=4, C=4096, T=32768, res_mode="sk"),
+    # The paper's own hidden sizes (App. A, scale-specific hyperparameters: S / M / L)
+    # at its per-GPU micro-batch of 16 sequences x 1024 tokens (App. A, shared
+    # hyperparameters), n = 4 (Sec. 4).
+    "paper_s_c512": Workload("paper_s_c512", n=4, C=512, T=16384),
+    "paper_m_c768": Workload("paper_m_c768", n=4, C=768, T=16384),
+    "paper_l_c1024": Workload("paper_l_c1024", n=4, C=1024, T=16384),
 }
 
 

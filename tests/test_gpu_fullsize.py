@@ -21,7 +21,8 @@ from gpu_harness import GpuLayer, desc_for, oracle_reference, rel_err, to_np64
 
 pytestmark = pytest.mark.gpu
 
-FULL = ["n4_c2048_fwd", "n4_c4096", "n3_c1024", "n5_c2560", "n4_c4096_sk"]
+FULL = ["n4_c2048_fwd", "n4_c4096", "n3_c1024", "n5_c2560", "n4_c4096_sk",
+        "paper_s_c512", "paper_m_c768", "paper_l_c1024"]
 
 
 def _sample_tokens(T, seed=7, extra=12):
@@ -73,7 +74,8 @@ def test_full_size_sampled_tokens(name):
         assert torch.isfinite(L.g_W).all() and torch.isfinite(L.g_x.float()).all()
 
 
-@pytest.mark.parametrize("name", ["n4_c4096", "n3_c1024", "n5_c2560", "n4_c4096_sk"])
+@pytest.mark.parametrize("name", ["n4_c4096", "n3_c1024", "n5_c2560", "n4_c4096_sk",
+                                  "paper_s_c512", "paper_m_c768", "paper_l_c1024"])
 def test_full_size_parameter_gradients(name):
     wl = si.WORKLOADS[name]
     print(f"case {wl}", flush=True)
