@@ -170,6 +170,37 @@ int mhcl_bwd_fused(const mhcl_desc *desc, const void *x, const void *y, const fl
                    void *g_x, void *g_y, float *g_W, float *g_b, float *g_alpha,
                    void *ws, size_t ws_bytes, void *stream);
 
+/* ---- diagnostics of doubly stochasticity (Sec. 3.1, Sec. 4.3) ------------ */
+
+/* The logits of one layer, z = alpha_g (RMSNorm(x_hat) W) + b (Sec. 3.2, the
+ * three lines above Eq. 4; Sec. 2 Eq. 2 in SK mode), and per token the
+ * relative range of Eq. 3 for the matrix exp(mat(z_res)) that Sinkhorn-Knopp
+ * starts from, as log(1/nu) = max z_res - min z_res (natural log; every entry
+ * of exp(.) is positive, so the minimum over positive entries is the minimum).
+ * in : x [T,n,C] io, W [nC,M] f32, b [M] f32, alpha [3] f32
+ * out: z [T,M] f32, columns [res | pre | post]; log_inv_nu [T] f32.  Either
+ *      output may be null, not both.
+ * Workspace as for MHCL_OP_COEFFS. */
+int mhcl_logits(const mhcl_desc *desc, const void *x, const float *W, const float *b,
+                const float *alpha, float *z, float *log_inv_nu, void *ws, size_t ws_bytes,
+                void *stream);
+
+/* Column sums and l1 errors of L layers' per-token residual matrices and of
+ * their running product over the layers (Sec. 3.1 footnote 1 and last
+ * paragraph; Sec. 4.3, "per-matrix" and "prod").  n in 1..5, L >= 1, T >= 0.
+ * in : H [L,T,n,n] f32 (e.g. L calls of mhcl_coeffs into one buffer)
+ * out, each nullable (not all):
+ *   colsum      [L,T,n]  colsum[l][t][j] = sum_i H[l][t][i][j]
+ *   l1          [L,T]    ||H 1 - 1||_1 + ||H^T 1 - 1||_1
+ *   prod        [T,n,n]  Q_L, with Q_l = H_l Q_{l-1}, Q_0 = I: later layers
+ *                        multiply on the left, the order Eq. 1 applies them
+ *                        (the paper's product sign fixes no order)
+ *   prod_colsum [L,T,n]  column sums of Q_l
+ *   prod_l1     [L,T]    l1 error of Q_l
+ * fp32 throughout; needs no workspace. */
+int mhcl_ds_chain(int32_t n, int32_t L, int64_t T, const float *H, float *colsum, float *l1,
+                  float *prod, float *prod_colsum, float *prod_l1, void *stream);
+
 /* ---- measurement aids (no part of the method) --------------------------- */
 
 /* Kernel stages that can be bracketed with events. */

@@ -24,6 +24,7 @@ _SYMBOLS = [
     "mhcl_status_string", "mhcl_validate", "mhcl_logit_count", "mhcl_workspace_bytes",
     "mhcl_perm_table", "mhcl_coeffs", "mhcl_pre", "mhcl_post", "mhcl_fwd_coeffs_pre",
     "mhcl_post_bwd", "mhcl_pre_bwd", "mhcl_coeffs_bwd", "mhcl_bwd_fused",
+    "mhcl_logits", "mhcl_ds_chain", "mhcl_profile_next_call", "mhcl_debug_copy",
 ]
 
 
@@ -93,6 +94,8 @@ def lib():
         L.mhcl_pre_bwd.argtypes = [P] + [V] * 6
         L.mhcl_coeffs_bwd.argtypes = [P] + [V] * 12 + [Z, V]
         L.mhcl_bwd_fused.argtypes = [P] + [V] * 13 + [Z, V]
+        L.mhcl_logits.argtypes = [P] + [V] * 7 + [Z, V]
+        L.mhcl_ds_chain.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int64] + [V] * 7
         _lib = L
     return _lib
 
@@ -232,3 +235,21 @@ def mhcl_bwd_fused(d, x, y, W, b, alpha, g_xout, g_h, g_x, g_y, g_W, g_b, g_alph
         _ptr(g_y, io, (d.T, d.C), "g_y"), _ptr(g_W, f, (d.n * d.C, d.M), "g_W"),
         _ptr(g_b, f, (d.M,), "g_b"), _ptr(g_alpha, f, (3,), "g_alpha"), wp, wb, _stream()),
         "mhcl_bwd_fused")
+
+
+def mhcl_logits(d, x, W, b, alpha, z, log_inv_nu, ws):
+    f, io = torch.float32, d.torch_dtype
+    wp, wb = _ws(ws)
+    _check(lib().mhcl_logits(
+        ctypes.byref(d.c), _ptr(x, io, (d.T, d.n, d.C), "x"), _ptr(W, f, (d.n * d.C, d.M), "W"),
+        _ptr(b, f, (d.M,), "b"), _ptr(alpha, f, (3,), "alpha"), _ptr(z, f, (d.T, d.M), "z"),
+        _ptr(log_inv_nu, f, (d.T,), "log_inv_nu"), wp, wb, _stream()), "mhcl_logits")
+
+
+def mhcl_ds_chain(n, L, T, H, colsum, l1, prod, prod_colsum, prod_l1):
+    f = torch.float32
+    _check(lib().mhcl_ds_chain(
+        n, L, T, _ptr(H, f, (L, T, n, n), "H"), _ptr(colsum, f, (L, T, n), "colsum"),
+        _ptr(l1, f, (L, T), "l1"), _ptr(prod, f, (T, n, n), "prod"),
+        _ptr(prod_colsum, f, (L, T, n), "prod_colsum"), _ptr(prod_l1, f, (L, T), "prod_l1"),
+        _stream()), "mhcl_ds_chain")

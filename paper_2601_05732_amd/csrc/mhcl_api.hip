@@ -206,6 +206,40 @@ int mhcl_coeffs(const mhcl_desc *desc, const void *x, const float *W, const floa
   return MHCL_OK;
 }
 
+int mhcl_logits(const mhcl_desc *desc, const void *x, const float *W, const float *b,
+                const float *alpha, float *z, float *log_inv_nu, void *ws, size_t ws_bytes,
+                void *stream) {
+  if (int e = check_desc(desc)) return e;
+  if (desc->T == 0) return MHCL_OK;   // per-token tensors may then be null
+  if (!all_ok(x, (const void *)W, (const void *)b, (const void *)alpha))
+    return MHCL_ERR_INVALID_ARG;
+  if ((!z && !log_inv_nu) || !aligned16(z) || !aligned16(log_inv_nu)) return MHCL_ERR_INVALID_ARG;
+  if (!ws || !aligned16(ws) || ws_bytes < mhcl_workspace_bytes(desc, MHCL_OP_COEFFS))
+    return MHCL_ERR_WORKSPACE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  CoeffsWs w(*desc, ws);
+  Disarm disarm;
+  MHCL_HIP(run_projection(*desc, x, W, w.u_raw, w.sumsq, w.Wp, MHCL_STAGE_FWD_PROJ, s));
+  MHCL_HIP(launch_logits(*desc, mhcl_logit_count(desc), proj_ksplit(*desc), w.u_raw, w.sumsq, b,
+                         alpha, z, log_inv_nu, s));
+  return MHCL_OK;
+}
+
+int mhcl_ds_chain(int32_t n, int32_t L, int64_t T, const float *H, float *colsum, float *l1,
+                  float *prod, float *prod_colsum, float *prod_l1, void *stream) {
+  if (n < 1 || n > kMaxN || L < 1 || T < 0) return MHCL_ERR_INVALID_ARG;
+  if (T == 0) return MHCL_OK;
+  if (!H || !aligned16(H)) return MHCL_ERR_INVALID_ARG;
+  if (!colsum && !l1 && !prod && !prod_colsum && !prod_l1) return MHCL_ERR_INVALID_ARG;
+  if (!aligned16(colsum) || !aligned16(l1) || !aligned16(prod) || !aligned16(prod_colsum) ||
+      !aligned16(prod_l1))
+    return MHCL_ERR_INVALID_ARG;
+  Disarm disarm;
+  MHCL_HIP(launch_ds_chain(n, L, T, H, colsum, l1, prod, prod_colsum, prod_l1,
+                           static_cast<hipStream_t>(stream)));
+  return MHCL_OK;
+}
+
 int mhcl_pre(const mhcl_desc *desc, const void *x, const float *H_pre, void *h, void *stream) {
   if (int e = check_desc(desc)) return e;
   if (desc->T == 0) return MHCL_OK;   // per-token tensors may then be null

@@ -75,6 +75,14 @@ int param_sum_blocks(const mhcl_desc &d);
 hipError_t launch_param_sums(const mhcl_desc &d, int M, const float *gz, float *g_b, float *g_alpha,
                              float *part, hipStream_t s);
 
+// ---- diagnostics ----------------------------------------------------------
+// z [T,M] and spread [T] (max - min of the residual logits); either may be null
+hipError_t launch_logits(const mhcl_desc &d, int M, int parts, const float *u_raw,
+                         const float *sumsq, const float *b, const float *alpha, float *z,
+                         float *spread, hipStream_t s);
+hipError_t launch_ds_chain(int n, int L, int64_t T, const float *H, float *colsum, float *l1,
+                           float *prod, float *prod_colsum, float *prod_l1, hipStream_t s);
+
 // ---- bf16 fast path (MFMA projections); needs fast_path_ok(desc) ---------
 bool fast_path_ok(const mhcl_desc &d);
 // The MFMA projection may split K over up to kMaxKSplit blocks per token tile;

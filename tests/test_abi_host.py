@@ -72,6 +72,15 @@ def test_null_and_misaligned_pointers_fail_before_any_launch():
     assert L.mhcl_bwd_fused(ctypes.byref(d.c), *([ok] * 12), None, 0, None) == 3
     assert L.mhcl_coeffs(None, ok, ok, ok, ok, ok, ok, ok, ok, 1 << 20, None) == 1
     assert mhcl.lib().mhcl_status_string(3).decode().startswith("workspace")
+    # diagnostics
+    assert L.mhcl_logits(ctypes.byref(d.c), ok, ok, ok, ok, None, None, ok, 1 << 20, None) == 1
+    assert L.mhcl_logits(ctypes.byref(d.c), ok, ok, ok, ok, ok, None, None, 0, None) == 3
+    assert L.mhcl_ds_chain(4, 2, 16, None, ok, ok, ok, ok, ok, None) == 1
+    assert L.mhcl_ds_chain(4, 2, 16, ok, None, None, None, None, None, None) == 1
+    assert L.mhcl_ds_chain(6, 2, 16, ok, ok, ok, ok, ok, ok, None) == 1
+    assert L.mhcl_ds_chain(4, 0, 16, ok, ok, ok, ok, ok, ok, None) == 1
+    assert L.mhcl_ds_chain(4, 2, 16, ok, ok + 4, ok, ok, ok, ok, None) == 1
+    assert L.mhcl_ds_chain(4, 2, 0, None, None, None, None, None, None, None) == 0
 
 
 def test_binding_refuses_cpu_tensors():
