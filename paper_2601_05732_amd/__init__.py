@@ -12,3 +12,4 @@ from .binding import (  # noqa: F401
     mhcl_coeffs_bwd, mhcl_bwd_fused, mhcl_logits, mhcl_ds_chain,
 )
 from .layer import GpuLayer, desc_for  # noqa: F401,E402
+from .autograd import HyperConnection, HyperConnectionStack, init_params  # noqa: F401,E402
