@@ -392,7 +392,7 @@ int mhcl_bwd_fused(const mhcl_desc *desc, const void *x, const void *y, const fl
       StageBracket br(MHCL_STAGE_BWD_OUT, s);
       MHCL_HIP(launch_bwd_out_gw(*desc, M, x, g_xout, g_h, f, g_x, g_y, g_W, s));
     }
-    MHCL_HIP(launch_param_sums(*desc, M, f.gz, g_b, g_alpha, f.psum, s));
+    MHCL_HIP(launch_param_sums_rows((desc->T + 63) / 64, M, f.gz, g_b, g_alpha, f.psum, s));
     return MHCL_OK;
   }
   BwdWs w(*desc, ws, true);

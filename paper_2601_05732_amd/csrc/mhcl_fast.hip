@@ -428,77 +428,95 @@ __global__ __launch_bounds__(256, 2) void bwd_reduce_kernel(
 //   cpk  [T][CP] f32 : H_res (N*N) | H_pre (N) | H_post (N) | coefx
 //   vr   [Tpad][MP32] bf16 hi, lo : vr = r alpha g_z, row per token
 //   vrT  [Tpad/32][MP16][32] bf16 hi, lo : the same, tokens innermost
-//   gz   [T][M+3] f32 : g_z and the per-group sums of g_z u (for g_b, g_alpha)
+//   gzs  [Tpad/64][M+3] f32 : per 64 tokens, the sums of g_z and of the per-group
+//        g_z u (what g_b and g_alpha are summed from), in a fixed butterfly order
 // Tokens T..Tpad-1 get zero vr so that padded tiles add nothing to g_W.
+// One wave per block, one token per lane.
 template <int N, int MODE>
-__global__ __launch_bounds__(128) void bwd_epilogue_fast_kernel(
+__global__ __launch_bounds__(64) void bwd_epilogue_fast_kernel(
     const float *__restrict__ u_raw, const float *__restrict__ sumsq, int parts,
     const float *__restrict__ b, const float *__restrict__ alpha, const float *__restrict__ gH_res,
     const float *__restrict__ gH_pre, const float *__restrict__ gH_post, int nC, float eps,
-    int sk_iters, int64_t T, int64_t Tpad, int CP, int MP32, int MP16, float *__restrict__ cpk,
-    uint16_t *__restrict__ vr_hi, uint16_t *__restrict__ vr_lo, uint16_t *__restrict__ vrT_hi,
-    uint16_t *__restrict__ vrT_lo, float *__restrict__ gz_out) {
+    int sk_iters, int64_t T, int CP, float *__restrict__ cpk, uint16_t *__restrict__ vr_hi,
+    uint16_t *__restrict__ vr_lo, uint16_t *__restrict__ vrT_hi, uint16_t *__restrict__ vrT_lo,
+    float *__restrict__ gz_sums) {
   constexpr int R = Dims<N, MODE>::R, M = Dims<N, MODE>::M;
-  const int64_t t = static_cast<int64_t>(blockIdx.x) * 128 + threadIdx.x;
-  if (t >= Tpad) return;
+  constexpr int MP32 = (M + 31) / 32 * 32, MP16 = (M + 15) / 16 * 16;
+  const int64_t t = static_cast<int64_t>(blockIdx.x) * 64 + threadIdx.x;   // < Tpad
   const int64_t blk = t >> 5;
   const int tin = static_cast<int>(t & 31);
-  if (t >= T) {
-    for (int m = 0; m < MP32; ++m) { vr_hi[t * MP32 + m] = 0; vr_lo[t * MP32 + m] = 0; }
-    for (int m = 0; m < MP16; ++m) {
-      vrT_hi[(blk * MP16 + m) * 32 + tin] = 0;
-      vrT_lo[(blk * MP16 + m) * 32 + tin] = 0;
-    }
-    return;
-  }
-  float u[M], bb[M], a[R], Hr[N * N], Hp[N], Hq[N], gz[M];
+  const bool live = t < T;
+  const int64_t tl = live ? t : T - 1;   // padded lanes recompute the last token and discard it
+  float u[M], a[R], Hr[N * N], Hp[N], Hq[N], gz[M + 3];
   float gr[N * N], gp[N], gq[N];
   float sums[(MODE == MHCL_RES_SK) ? 2 * kMaxSkIters * N : 1];
-  float ssq = sumsq[t];
+  float ssq = sumsq[tl];
 #pragma unroll
-  for (int m = 0; m < M; ++m) { u[m] = u_raw[t * M + m]; bb[m] = b[m]; }
+  for (int m = 0; m < M; ++m) u[m] = u_raw[tl * M + m];
   for (int pt = 1; pt < parts; ++pt) {   // K-split slices of the projection, added in order
-    ssq += sumsq[pt * T + t];
+    ssq += sumsq[pt * T + tl];
 #pragma unroll
-    for (int m = 0; m < M; ++m) u[m] += u_raw[(pt * T + t) * M + m];
+    for (int m = 0; m < M; ++m) u[m] += u_raw[(pt * T + tl) * M + m];
   }
 #pragma unroll
-  for (int e = 0; e < N * N; ++e) gr[e] = gH_res[t * N * N + e];
+  for (int e = 0; e < N * N; ++e) gr[e] = gH_res[tl * N * N + e];
 #pragma unroll
-  for (int j = 0; j < N; ++j) { gp[j] = gH_pre[t * N + j]; gq[j] = gH_post[t * N + j]; }
+  for (int j = 0; j < N; ++j) { gp[j] = gH_pre[tl * N + j]; gq[j] = gH_post[tl * N + j]; }
   const TokenParams p{alpha[0], alpha[1], alpha[2], eps, sk_iters};
-  const float r = token_coeffs<N, MODE>(u, ssq, nC, bb, p, Hr, Hp, Hq, a,
+  const float r = token_coeffs<N, MODE>(u, ssq, nC, b, p, Hr, Hp, Hq, a,
                                         (MODE == MHCL_RES_SK) ? sums : nullptr);
-  float *cp = cpk + t * CP;
+  if (live) {
+    float *cp = cpk + t * CP;
 #pragma unroll
-  for (int e = 0; e < N * N; ++e) cp[e] = Hr[e];
+    for (int e = 0; e < N * N; ++e) cp[e] = Hr[e];
 #pragma unroll
-  for (int j = 0; j < N; ++j) { cp[N * N + j] = Hp[j]; cp[N * N + N + j] = Hq[j]; }
+    for (int j = 0; j < N; ++j) { cp[N * N + j] = Hp[j]; cp[N * N + N + j] = Hq[j]; }
+  }
   token_coeffs_bwd<N, MODE>(gr, gp, gq, a, Hr, Hp, Hq, sums, sk_iters, gz);
   float ga[3] = {0.f, 0.f, 0.f}, dot = 0.f;
+  uint32_t ph[MP32 / 2], pl[MP32 / 2];   // the token's vr row, two bf16 per word
+#pragma unroll
+  for (int i = 0; i < MP32 / 2; ++i) { ph[i] = 0; pl[i] = 0; }
 #pragma unroll
   for (int m = 0; m < M; ++m) {
     const int g = m < R ? 0 : (m < R + N ? 1 : 2);
     const float al = g == 0 ? p.alpha_res : (g == 1 ? p.alpha_pre : p.alpha_post);
+    if (!live) gz[m] = 0.f;
     const float vr = r * al * gz[m];
-    gz_out[t * (M + 3) + m] = gz[m];
     ga[g] += gz[m] * (r * u[m]);
     dot += vr * u[m];
     uint16_t hi, lo;
     split_bf16(vr, hi, lo);
-    vr_hi[t * MP32 + m] = hi;
-    vr_lo[t * MP32 + m] = lo;
+    ph[m / 2] |= static_cast<uint32_t>(hi) << (16 * (m & 1));
+    pl[m / 2] |= static_cast<uint32_t>(lo) << (16 * (m & 1));
     vrT_hi[(blk * MP16 + m) * 32 + tin] = hi;
     vrT_lo[(blk * MP16 + m) * 32 + tin] = lo;
   }
-  for (int m = M; m < MP32; ++m) { vr_hi[t * MP32 + m] = 0; vr_lo[t * MP32 + m] = 0; }
+#pragma unroll
   for (int m = M; m < MP16; ++m) {
     vrT_hi[(blk * MP16 + m) * 32 + tin] = 0;
     vrT_lo[(blk * MP16 + m) * 32 + tin] = 0;
   }
+  u32x4 *rh = reinterpret_cast<u32x4 *>(vr_hi + t * MP32);
+  u32x4 *rl = reinterpret_cast<u32x4 *>(vr_lo + t * MP32);
 #pragma unroll
-  for (int g = 0; g < 3; ++g) gz_out[t * (M + 3) + M + g] = ga[g];
-  cp[N * N + 2 * N] = (r * r / static_cast<float>(nC)) * dot;
+  for (int i = 0; i < MP32 / 8; ++i) {
+    rh[i] = u32x4{ph[4 * i], ph[4 * i + 1], ph[4 * i + 2], ph[4 * i + 3]};
+    rl[i] = u32x4{pl[4 * i], pl[4 * i + 1], pl[4 * i + 2], pl[4 * i + 3]};
+  }
+  if (live) cpk[t * CP + N * N + 2 * N] = (r * r / static_cast<float>(nC)) * dot;
+#pragma unroll
+  for (int g = 0; g < 3; ++g) gz[M + g] = ga[g];   // zero for padded lanes
+  // sum over the 64 tokens of the wave: butterfly, the same order in every run
+#pragma unroll
+  for (int m = 0; m < M + 3; ++m) {
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) gz[m] += __shfl_xor(gz[m], off, 64);
+  }
+  if (threadIdx.x == 0) {
+#pragma unroll
+    for (int m = 0; m < M + 3; ++m) gz_sums[static_cast<int64_t>(blockIdx.x) * (M + 3) + m] = gz[m];
+  }
 }
 
 // ---------------------------------------------------------------------------
@@ -1252,7 +1270,7 @@ FastBwdWs::FastBwdWs(const mhcl_desc &d, void *ws) {
   gH_pre = c.take<float>(T * n);
   gH_post = c.take<float>(T * n);
   cpk = c.take<float>(T * CP);
-  gz = c.take<float>(T * (M + 3));
+  gz = c.take<float>((Tpad / 64) * (M + 3));
   vr_hi = c.take<uint16_t>(Tpad * MP32);
   vr_lo = c.take<uint16_t>(Tpad * MP32);
   vrT_hi = c.take<uint16_t>(Tpad * MP16);
@@ -1310,10 +1328,11 @@ hipError_t launch_bwd_epilogue_fast(const mhcl_desc &d, const float *b, const fl
   const int64_t Tpad = (d.T + 63) / 64 * 64;
   auto go = [&](auto nn, auto mm) {
     constexpr int N = decltype(nn)::value, MODE = decltype(mm)::value;
-    hipLaunchKernelGGL((bwd_epilogue_fast_kernel<N, MODE>),
-                       dim3(static_cast<unsigned>((Tpad + 127) / 128)), dim3(128), 0, s, w.u_raw,
-                       w.sumsq, w.parts, b, alpha, w.gH_res, w.gH_pre, w.gH_post, d.n * d.C, d.eps,
-                       d.sk_iters, d.T, Tpad, w.CP, w.MP32, w.MP16, w.cpk, w.vr_hi, w.vr_lo,
+    if (w.MP32 != (Dims<N, MODE>::M + 31) / 32 * 32 || w.MP16 != (Dims<N, MODE>::M + 15) / 16 * 16)
+      return hipErrorInvalidValue;
+    hipLaunchKernelGGL((bwd_epilogue_fast_kernel<N, MODE>), dim3(static_cast<unsigned>(Tpad / 64)),
+                       dim3(64), 0, s, w.u_raw, w.sumsq, w.parts, b, alpha, w.gH_res, w.gH_pre,
+                       w.gH_post, d.n * d.C, d.eps, d.sk_iters, d.T, w.CP, w.cpk, w.vr_hi, w.vr_lo,
                        w.vrT_hi, w.vrT_lo, w.gz);
     return hipGetLastError();
   };

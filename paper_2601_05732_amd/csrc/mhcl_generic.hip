@@ -743,18 +743,26 @@ hipError_t launch_fill_zero(float *p, size_t count, hipStream_t s) {
   return hipGetLastError();
 }
 
-hipError_t launch_param_sums(const mhcl_desc &d, int M, const float *gz, float *g_b, float *g_alpha,
-                             float *part, hipStream_t s) {
+hipError_t launch_param_sums_rows(int64_t rows, int M, const float *src, float *g_b,
+                                  float *g_alpha, float *part, hipStream_t s) {
   const int ld = M + 3;
-  const int nblocks = param_sum_blocks(d);
-  const int64_t rpb = (d.T + nblocks - 1) / nblocks;
-  hipLaunchKernelGGL(colsum_stage1_kernel, dim3(nblocks), dim3(kBlock), 0, s, gz, d.T, ld, rpb,
+  int64_t nb = (rows + 127) / 128;
+  if (nb > 256) nb = 256;
+  if (nb < 1) nb = 1;
+  const int nblocks = static_cast<int>(nb);
+  const int64_t rpb = (rows + nblocks - 1) / nblocks;
+  hipLaunchKernelGGL(colsum_stage1_kernel, dim3(nblocks), dim3(kBlock), 0, s, src, rows, ld, rpb,
                      part);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(colsum_stage2_kernel, dim3(1), dim3(kBlock), 0, s, (const float *)part,
                      nblocks, ld, M, g_b, g_alpha);
   return hipGetLastError();
+}
+
+hipError_t launch_param_sums(const mhcl_desc &d, int M, const float *gz, float *g_b, float *g_alpha,
+                             float *part, hipStream_t s) {
+  return launch_param_sums_rows(d.T, M, gz, g_b, g_alpha, part, s);
 }
 
 int param_sum_blocks(const mhcl_desc &d) {

@@ -74,6 +74,9 @@ hipError_t launch_fill_zero(float *p, size_t count, hipStream_t s);
 int param_sum_blocks(const mhcl_desc &d);
 hipError_t launch_param_sums(const mhcl_desc &d, int M, const float *gz, float *g_b, float *g_alpha,
                              float *part, hipStream_t s);
+// the same over `rows` rows of [M+3] (rows <= T: `part` as above is large enough)
+hipError_t launch_param_sums_rows(int64_t rows, int M, const float *src, float *g_b,
+                                  float *g_alpha, float *part, hipStream_t s);
 
 // ---- diagnostics ----------------------------------------------------------
 // z [T,M] and spread [T] (max - min of the residual logits); either may be null
@@ -99,6 +102,7 @@ bool fast_bwd_ok(const mhcl_desc &d);
 bool fast_bwd_wide(const mhcl_desc &d);   // n = 5: pass 2 split into W vr and the mixing
 int gw_chunks_fast(const mhcl_desc &d);
 struct FastBwdWs {
+  // gz: [ceil(T/64)][M+3] sums of g_z and g_z u over each 64 tokens
   float *u_raw, *sumsq, *gH_res, *gH_pre, *gH_post, *cpk, *gz, *partials, *psum, *D;
   uint16_t *vr_hi, *vr_lo, *vrT_hi, *vrT_lo;
   char *Wp, *Wa;
