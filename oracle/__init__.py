@@ -83,6 +83,28 @@ def coeffs_lite(x, W, b, alpha, eps=1e-6, return_a=False):
     return (H_res, H_pre, H_post, a) if return_a else (H_res, H_pre, H_post)
 
 
+def _sigma32(sigma, n):
+    sigma = np.ascontiguousarray(np.asarray(sigma, dtype=np.int32))
+    assert sigma.ndim == 2 and sigma.shape[1] == n
+    assert all(sorted(row) == list(range(n)) for row in sigma.tolist()), "rows must be permutations"
+    return sigma
+
+
+def coeffs_subset(x, W, b, alpha, sigma, eps=1e-6, return_a=False):
+    """Permutation form restricted to the K permutations sigma [K, n]."""
+    x, W, b, alpha = _f64(x), _f64(W), _f64(b), _f64(alpha)
+    T, n, C = x.shape
+    sigma = _sigma32(sigma, n)
+    K = sigma.shape[0]
+    assert W.shape == (n * C, K + 2 * n) and b.shape == (K + 2 * n,) and alpha.shape == (3,)
+    H_res = np.empty((T, n, n)); H_pre = np.empty((T, n)); H_post = np.empty((T, n))
+    a = np.empty((T, K))
+    _load().mhclo_coeffs_subset(*_dims(x), ctypes.c_int(K), sigma.ctypes.data_as(_I), _p(x), _p(W),
+                                _p(b), _p(alpha), ctypes.c_double(eps), _p(H_res), _p(H_pre),
+                                _p(H_post), _p(a))
+    return (H_res, H_pre, H_post, a) if return_a else (H_res, H_pre, H_post)
+
+
 def sk(X0, iters=20):
     X0 = _f64(X0)
     n = X0.shape[0]
@@ -145,7 +167,7 @@ def pre_bwd(x, H_pre, g_h, g_x):
 
 
 def coeffs_bwd(x, W, b, alpha, g_H_res, g_H_pre, g_H_post, g_x, eps=1e-6, res_mode="lite",
-               iters=20):
+               iters=20, sigma=None):
     """g_x is accumulated into in place.  -> g_W, g_b, g_alpha"""
     x, W, b, alpha, g_H_res, g_H_pre, g_H_post = map(
         _f64, (x, W, b, alpha, g_H_res, g_H_pre, g_H_post))
@@ -158,6 +180,13 @@ def coeffs_bwd(x, W, b, alpha, g_H_res, g_H_pre, g_H_post, g_x, eps=1e-6, res_mo
         lib.mhclo_coeffs_lite_bwd(*_dims(x), _p(x), _p(W), _p(b), _p(alpha), ctypes.c_double(eps),
                                   _p(g_H_res), _p(g_H_pre), _p(g_H_post),
                                   _p(g_x), _p(g_W), _p(g_b), _p(g_alpha))
+    elif res_mode == "subset":
+        sigma = _sigma32(sigma, n)
+        assert W.shape[1] == sigma.shape[0] + 2 * n
+        lib.mhclo_coeffs_subset_bwd(*_dims(x), ctypes.c_int(sigma.shape[0]),
+                                    sigma.ctypes.data_as(_I), _p(x), _p(W), _p(b), _p(alpha),
+                                    ctypes.c_double(eps), _p(g_H_res), _p(g_H_pre), _p(g_H_post),
+                                    _p(g_x), _p(g_W), _p(g_b), _p(g_alpha))
     else:
         assert W.shape[1] == n * n + 2 * n
         lib.mhclo_coeffs_sk_bwd(*_dims(x), _p(x), _p(W), _p(b), _p(alpha), ctypes.c_double(eps),
@@ -182,11 +211,11 @@ def relative_range(X):
     return nu
 
 
-def logits(x, W, b, alpha, eps=1e-6, res_mode="lite"):
+def logits(x, W, b, alpha, eps=1e-6, res_mode="lite", n_perm=None):
     """z [T, M]: all logits, columns [res | pre | post]."""
     x, W, b, alpha = _f64(x), _f64(W), _f64(b), _f64(alpha)
     T, n, C = x.shape
-    R = math.factorial(n) if res_mode == "lite" else n * n
+    R = {"lite": math.factorial(n), "sk": n * n, "subset": n_perm}[res_mode]
     M = R + 2 * n
     assert W.shape == (n * C, M) and b.shape == (M,) and alpha.shape == (3,)
     z = np.empty((T, M))
@@ -208,10 +237,12 @@ def ds_chain(H):
     return out
 
 
-def forward(x, W, b, alpha, y, eps=1e-6, res_mode="lite", iters=20):
+def forward(x, W, b, alpha, y, eps=1e-6, res_mode="lite", iters=20, sigma=None):
     """Whole forward of one layer with y = f(h) supplied: coefficients, h, x_out."""
     if res_mode == "lite":
         H_res, H_pre, H_post = coeffs_lite(x, W, b, alpha, eps)
+    elif res_mode == "subset":
+        H_res, H_pre, H_post = coeffs_subset(x, W, b, alpha, sigma, eps)
     else:
         H_res, H_pre, H_post = coeffs_sk(x, W, b, alpha, eps, iters)
     h = pre(x, H_pre)
@@ -219,13 +250,13 @@ def forward(x, W, b, alpha, y, eps=1e-6, res_mode="lite", iters=20):
     return {"H_res": H_res, "H_pre": H_pre, "H_post": H_post, "h": h, "x_out": x_out}
 
 
-def backward(x, W, b, alpha, y, g_xout, g_h, eps=1e-6, res_mode="lite", iters=20):
+def backward(x, W, b, alpha, y, g_xout, g_h, eps=1e-6, res_mode="lite", iters=20, sigma=None):
     """Whole backward of one layer for L = <g_xout, x_out> + <g_h, h> with y an
     independent input: the three separable backwards chained."""
-    fw = forward(x, W, b, alpha, y, eps, res_mode, iters)
+    fw = forward(x, W, b, alpha, y, eps, res_mode, iters, sigma)
     g_x, g_y, g_H_res, g_H_post = post_bwd(x, y, fw["H_res"], fw["H_post"], g_xout)
     g_H_pre = pre_bwd(x, fw["H_pre"], g_h, g_x)
     g_W, g_b, g_alpha = coeffs_bwd(x, W, b, alpha, g_H_res, g_H_pre, g_H_post, g_x, eps,
-                                   res_mode, iters)
+                                   res_mode, iters, sigma)
     return {"g_x": g_x, "g_y": g_y, "g_W": g_W, "g_b": g_b, "g_alpha": g_alpha,
             "g_H_res": g_H_res, "g_H_pre": g_H_pre, "g_H_post": g_H_post, **fw}

@@ -14,6 +14,7 @@
  *   coefficients, Sinkhorn-Knopp form ... Sec. 2, Eq. (2) and the three lines
  *                                         above it; SK as described in Sec. 1
  *                                         and below Eq. (2) (20 repetitions)
+ *   coefficients, permutation subset .... Sec. 5, paragraph on larger n
  *   stream mixing ........................ Sec. 2, Eq. (1)
  *   l1 error, relative range ............. Sec. 3.1, footnote 1 and Eq. (3)
  *   column sums, product over layers ..... Sec. 3.1 last paragraph, Sec. 4.3
@@ -33,8 +34,10 @@
  * forward, the paper's 3x3 SK example, central finite differences and a
  * library autograd for every backward; for the diagnostics, composition of
  * permutations, scaled doubly stochastic chains in closed form, a library
- * matrix product and the printed column sums of the 3x3 example.  No function
- * here is unpinned.
+ * matrix product and the printed column sums of the 3x3 example; for the
+ * permutation subset, bitwise equality with the full form when all n! are
+ * given, circulant closed form, single-permutation and one-hot cases, finite
+ * differences.  No function here is unpinned.
  *
  * All arrays are dense row-major doubles.  Tokens are independent; loops over
  * tokens are OpenMP-parallel, every sum inside a token and every sum over
@@ -124,15 +127,13 @@ static void softmax(int R, const double *z, double *a)
 }
 
 /* Sec. 3.2: H_pre = sigmoid(.), H_post = 2 sigmoid(.), a = softmax(.),
- * H_res = sum_k a_k P_k (dense contraction with the 0/1 stack).
- * a_out (nullable) receives the weights a, [T][n!]. */
-void mhclo_coeffs_lite(int n, int C, long T, const double *x, const double *W, const double *b,
-                       const double *alpha, double eps,
-                       double *H_res, double *H_pre, double *H_post, double *a_out)
+ * H_res = sum_k a_k P_k (dense contraction with the 0/1 stack P [R][n][n]).
+ * a_out (nullable) receives the weights a, [T][R]. */
+static void coeffs_stack(int n, int C, long T, int R, const double *P, const double *x,
+                         const double *W, const double *b, const double *alpha, double eps,
+                         double *H_res, double *H_pre, double *H_post, double *a_out)
 {
-    int nC = n * C, R = mhclo_factorial(n), M = R + 2 * n;
-    double *P = (double *)malloc(sizeof(double) * (size_t)R * n * n);
-    mhclo_pstack(n, P);
+    int nC = n * C, M = R + 2 * n;
 #pragma omp parallel
     {
         double *xn = (double *)malloc(sizeof(double) * nC);
@@ -158,6 +159,38 @@ void mhclo_coeffs_lite(int n, int C, long T, const double *x, const double *W, c
         }
         free(xn); free(u); free(z); free(a);
     }
+}
+
+/* All n! permutations, lexicographic order (Sec. 3.2, Eqs. (4)-(5)). */
+void mhclo_coeffs_lite(int n, int C, long T, const double *x, const double *W, const double *b,
+                       const double *alpha, double eps,
+                       double *H_res, double *H_pre, double *H_post, double *a_out)
+{
+    int R = mhclo_factorial(n);
+    double *P = (double *)malloc(sizeof(double) * (size_t)R * n * n);
+    mhclo_pstack(n, P);
+    coeffs_stack(n, C, T, R, P, x, W, b, alpha, eps, H_res, H_pre, H_post, a_out);
+    free(P);
+}
+
+/* P[k][i][j] = 1 if sigma[k][i] == j for K given permutations. */
+static double *stack_of(int n, int K, const int *sigma)
+{
+    double *P = (double *)calloc((size_t)K * n * n, sizeof(double));
+    for (int k = 0; k < K; ++k)
+        for (int i = 0; i < n; ++i) P[((size_t)k * n + i) * n + sigma[k * n + i]] = 1.0;
+    return P;
+}
+
+/* The same with only K chosen permutations sigma [K][n] (Sec. 5, discussion
+ * of larger n: a subset of the permutation matrices; the result stays doubly
+ * stochastic).  Logit columns [K | n | n]. */
+void mhclo_coeffs_subset(int n, int C, long T, int K, const int *sigma, const double *x,
+                         const double *W, const double *b, const double *alpha, double eps,
+                         double *H_res, double *H_pre, double *H_post, double *a_out)
+{
+    double *P = stack_of(n, K, sigma);
+    coeffs_stack(n, C, T, K, P, x, W, b, alpha, eps, H_res, H_pre, H_post, a_out);
     free(P);
 }
 
@@ -364,16 +397,14 @@ static void logits_bwd(int n, int C, long T, int R, const double *x, const doubl
     free(v); free(rr); free(uu);
 }
 
-/* Backward of mhclo_coeffs_lite.  Recomputes the forward from x.  g_x is
+/* Backward of coeffs_stack.  Recomputes the forward from x.  g_x is
  * accumulated into; g_W, g_b, g_alpha are overwritten. */
-void mhclo_coeffs_lite_bwd(int n, int C, long T, const double *x, const double *W, const double *b,
-                           const double *alpha, double eps,
-                           const double *g_H_res, const double *g_H_pre, const double *g_H_post,
-                           double *g_x, double *g_W, double *g_b, double *g_alpha)
+static void coeffs_stack_bwd(int n, int C, long T, int R, const double *P, const double *x,
+                             const double *W, const double *b, const double *alpha, double eps,
+                             const double *g_H_res, const double *g_H_pre, const double *g_H_post,
+                             double *g_x, double *g_W, double *g_b, double *g_alpha)
 {
-    int nC = n * C, R = mhclo_factorial(n), M = R + 2 * n;
-    double *P = (double *)malloc(sizeof(double) * (size_t)R * n * n);
-    mhclo_pstack(n, P);
+    int nC = n * C, M = R + 2 * n;
     double *g_z = (double *)malloc(sizeof(double) * (size_t)T * M);
 #pragma omp parallel
     {
@@ -407,7 +438,32 @@ void mhclo_coeffs_lite_bwd(int n, int C, long T, const double *x, const double *
         free(xn); free(u); free(z); free(a); free(g_a);
     }
     logits_bwd(n, C, T, R, x, W, alpha, eps, g_z, g_x, g_W, g_b, g_alpha);
-    free(g_z); free(P);
+    free(g_z);
+}
+
+void mhclo_coeffs_lite_bwd(int n, int C, long T, const double *x, const double *W, const double *b,
+                           const double *alpha, double eps,
+                           const double *g_H_res, const double *g_H_pre, const double *g_H_post,
+                           double *g_x, double *g_W, double *g_b, double *g_alpha)
+{
+    int R = mhclo_factorial(n);
+    double *P = (double *)malloc(sizeof(double) * (size_t)R * n * n);
+    mhclo_pstack(n, P);
+    coeffs_stack_bwd(n, C, T, R, P, x, W, b, alpha, eps, g_H_res, g_H_pre, g_H_post, g_x, g_W,
+                     g_b, g_alpha);
+    free(P);
+}
+
+void mhclo_coeffs_subset_bwd(int n, int C, long T, int K, const int *sigma, const double *x,
+                             const double *W, const double *b, const double *alpha, double eps,
+                             const double *g_H_res, const double *g_H_pre,
+                             const double *g_H_post, double *g_x, double *g_W, double *g_b,
+                             double *g_alpha)
+{
+    double *P = stack_of(n, K, sigma);
+    coeffs_stack_bwd(n, C, T, K, P, x, W, b, alpha, eps, g_H_res, g_H_pre, g_H_post, g_x, g_W,
+                     g_b, g_alpha);
+    free(P);
 }
 
 /* Backward of mhclo_coeffs_sk: re-runs SK keeping every half step, then walks
