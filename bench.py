@@ -163,7 +163,7 @@ def main():
     inp = si.make_inputs(wl, seed=0, device="cuda:0")
     if not wl.backward:
         raise SystemExit("bench.py times forward+backward; pick a workload with backward")
-    d = mhcl.desc_for(wl)
+    d = mhcl.desc_for(wl, perm=inp.get("perm"))
     L = mhcl.GpuLayer(d, inp)
     e = 2 if wl.io == "bf16" else 4
     lib = mhcl.lib()

@@ -17,7 +17,10 @@
  *
  * (P_k: the n! permutation matrices, Theorem 3.1), or, in the Sinkhorn-Knopp
  * variant (Sec. 2, Eq. 2), H_res = SK(exp(mat(alpha_res x_hat' W_res + b_res)))
- * with W_res in R^{nC x n^2} and SK repeated sk_iters times.
+ * with W_res in R^{nC x n^2} and SK repeated sk_iters times.  A third form
+ * keeps only K chosen permutations (Sec. 5, the paragraph on larger n):
+ * a = softmax over K logits, H_res = sum over the K given P_k; still doubly
+ * stochastic, n up to 8.
  *
  * f (attention / MLP) is the caller's: the library hands back h = H_pre x, the
  * caller computes y = f(h) and hands y in.  Backward likewise: the caller
@@ -40,7 +43,8 @@
  *  - x is [T, n, C] and is flattened stream-major: x_hat[j*C + c] = x[j][c].
  *  - W is one [n*C, M] matrix, b is [M]; columns are [res | pre | post] with
  *    M = n! + 2n (MHCL_RES_LITE; res column k belongs to permutation k) or
- *    M = n*n + 2n (MHCL_RES_SK; res column i*n + j is entry (i, j)).
+ *    M = n*n + 2n (MHCL_RES_SK; res column i*n + j is entry (i, j)), or
+ *    M = K + 2n (MHCL_RES_SUBSET; res column k belongs to row k of desc->perm).
  *    alpha is [3] = {alpha_res, alpha_pre, alpha_post}, in device memory.
  *  - Permutations are ordered lexicographically as tuples
  *    (sigma(0), ..., sigma(n-1)); k = 0 is the identity; P_k[i][sigma_k(i)] = 1.
@@ -72,7 +76,7 @@ typedef enum {
 } mhcl_status;
 
 enum { MHCL_BF16 = 0, MHCL_F32 = 1 };          /* io_dtype */
-enum { MHCL_RES_LITE = 0, MHCL_RES_SK = 1 };   /* res_mode */
+enum { MHCL_RES_LITE = 0, MHCL_RES_SK = 1, MHCL_RES_SUBSET = 2 };   /* res_mode */
 
 /* operations that need workspace, for mhcl_workspace_bytes() */
 enum {
@@ -83,13 +87,19 @@ enum {
 };
 
 typedef struct {
-  int32_t n;        /* residual streams, 1..5                                      */
+  int32_t n;        /* residual streams, 1..5 (1..8 for MHCL_RES_SUBSET)           */
   int32_t C;        /* width of one stream; a positive multiple of 8               */
   int64_t T;        /* tokens, >= 0                                                */
   int32_t io_dtype; /* MHCL_BF16 | MHCL_F32                                        */
-  int32_t res_mode; /* MHCL_RES_LITE | MHCL_RES_SK                                 */
-  int32_t sk_iters; /* SK repetitions (1..64) for MHCL_RES_SK; ignored for LITE    */
+  int32_t res_mode; /* MHCL_RES_LITE | MHCL_RES_SK | MHCL_RES_SUBSET               */
+  int32_t sk_iters; /* SK repetitions (1..32) for MHCL_RES_SK; else ignored         */
   float eps;        /* RMSNorm epsilon, >= 0, added to the mean square             */
+  int32_t n_perm;   /* MHCL_RES_SUBSET: K, number of permutations, 1..128; else ignored */
+  const int8_t *perm; /* MHCL_RES_SUBSET: DEVICE pointer, [K][n], perm[k][i] = column
+                       * of the 1 in row i of P_k.  Every row must be a permutation of
+                       * 0..n-1 (the caller's responsibility: device memory is not
+                       * inspected on the host); it must stay valid while kernels of a
+                       * call using this descriptor run.  Else ignored.           */
 } mhcl_desc;
 
 const char *mhcl_status_string(int status);
@@ -187,7 +197,7 @@ int mhcl_logits(const mhcl_desc *desc, const void *x, const float *W, const floa
 
 /* Column sums and l1 errors of L layers' per-token residual matrices and of
  * their running product over the layers (Sec. 3.1 footnote 1 and last
- * paragraph; Sec. 4.3, "per-matrix" and "prod").  n in 1..5, L >= 1, T >= 0.
+ * paragraph; Sec. 4.3, "per-matrix" and "prod").  n in 1..8, L >= 1, T >= 0.
  * in : H [L,T,n,n] f32 (e.g. L calls of mhcl_coeffs into one buffer)
  * out, each nullable (not all):
  *   colsum      [L,T,n]  colsum[l][t][j] = sum_i H[l][t][i][j]

@@ -17,7 +17,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libmhcl.so")
 
 BF16, F32 = 0, 1
-RES_LITE, RES_SK = 0, 1
+RES_LITE, RES_SK, RES_SUBSET = 0, 1, 2
 OP_COEFFS, OP_COEFFS_BWD, OP_FWD_COEFFS_PRE, OP_BWD_FUSED = 0, 1, 2, 3
 
 _SYMBOLS = [
@@ -37,19 +37,33 @@ class MhclError(RuntimeError):
 class _CDesc(ctypes.Structure):
     _fields_ = [("n", ctypes.c_int32), ("C", ctypes.c_int32), ("T", ctypes.c_int64),
                 ("io_dtype", ctypes.c_int32), ("res_mode", ctypes.c_int32),
-                ("sk_iters", ctypes.c_int32), ("eps", ctypes.c_float)]
+                ("sk_iters", ctypes.c_int32), ("eps", ctypes.c_float),
+                ("n_perm", ctypes.c_int32), ("perm", ctypes.c_void_p)]
 
 
 class Desc:
     """Mirror of ``mhcl_desc``."""
 
-    def __init__(self, n, C, T, io_dtype=BF16, res_mode=RES_LITE, sk_iters=20, eps=1e-6):
+    def __init__(self, n, C, T, io_dtype=BF16, res_mode=RES_LITE, sk_iters=20, eps=1e-6, perm=None):
+        """perm: for RES_SUBSET, an int8 GPU tensor [K, n] of permutations (kept alive here)."""
         self.n, self.C, self.T = int(n), int(C), int(T)
         self.io_dtype, self.res_mode, self.sk_iters, self.eps = io_dtype, res_mode, sk_iters, eps
-        self.c = _CDesc(self.n, self.C, self.T, io_dtype, res_mode, sk_iters, eps)
+        self.perm = perm
+        n_perm, pptr = 0, None
+        if perm is not None:
+            if perm.dtype != torch.int8 or perm.dim() != 2 or perm.shape[1] != self.n \
+                    or not perm.is_contiguous():
+                raise ValueError("perm must be a contiguous int8 tensor [K, n]")
+            if T > 0 and not perm.is_cuda:
+                raise ValueError("perm must be a GPU tensor")
+            n_perm, pptr = int(perm.shape[0]), perm.data_ptr()
+        self.n_perm = n_perm
+        self.c = _CDesc(self.n, self.C, self.T, io_dtype, res_mode, sk_iters, eps, n_perm, pptr)
 
     @property
     def R(self):
+        if self.res_mode == RES_SUBSET:
+            return self.n_perm
         return math.factorial(self.n) if self.res_mode == RES_LITE else self.n * self.n
 
     @property

@@ -10,11 +10,15 @@ bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 
 int check_desc(const mhcl_desc *d) {
   if (!d) return MHCL_ERR_INVALID_ARG;
-  if (d->n < 1 || d->n > kMaxN) return MHCL_ERR_INVALID_ARG;
+  if (d->res_mode != MHCL_RES_LITE && d->res_mode != MHCL_RES_SK && d->res_mode != MHCL_RES_SUBSET)
+    return MHCL_ERR_INVALID_ARG;
+  if (d->n < 1 || d->n > (d->res_mode == MHCL_RES_SUBSET ? kMaxNSubset : kMaxN))
+    return MHCL_ERR_INVALID_ARG;
+  if (d->res_mode == MHCL_RES_SUBSET && (d->n_perm < 1 || d->n_perm > kMaxPerm || !d->perm))
+    return MHCL_ERR_INVALID_ARG;
   if (d->C < 8 || d->C % 8 != 0) return MHCL_ERR_INVALID_ARG;
   if (d->T < 0) return MHCL_ERR_INVALID_ARG;
   if (d->io_dtype != MHCL_BF16 && d->io_dtype != MHCL_F32) return MHCL_ERR_INVALID_ARG;
-  if (d->res_mode != MHCL_RES_LITE && d->res_mode != MHCL_RES_SK) return MHCL_ERR_INVALID_ARG;
   if (d->res_mode == MHCL_RES_SK && (d->sk_iters < 1 || d->sk_iters > kMaxSkIters))
     return MHCL_ERR_INVALID_ARG;
   if (!(d->eps >= 0.f)) return MHCL_ERR_INVALID_ARG;
@@ -31,7 +35,7 @@ bool all_ok(P... p) {
   return ((p != nullptr && aligned16(p)) && ...);
 }
 
-int logits(const mhcl_desc &d) { return res_logits(d.n, d.res_mode) + 2 * d.n; }
+int logits(const mhcl_desc &d) { return res_logits(d) + 2 * d.n; }
 
 // ---- workspace layouts -----------------------------------------------------
 struct CoeffsWs {
@@ -118,6 +122,26 @@ hipError_t run_projection(const mhcl_desc &d, const void *x, const float *W, flo
   return launch_proj_generic(d, M, x, W, u_raw, sumsq, s);
 }
 
+// per-token coefficients from the projection: compile-time tables for the full
+// permutation and Sinkhorn-Knopp forms, the run-time table for a subset
+hipError_t run_coeffs_epilogue(const mhcl_desc &d, const float *u_raw, const float *sumsq,
+                               const float *b, const float *alpha, float *H_res, float *H_pre,
+                               float *H_post, hipStream_t s) {
+  if (d.res_mode == MHCL_RES_SUBSET)
+    return launch_coeffs_subset(d, proj_ksplit(d), u_raw, sumsq, b, alpha, H_res, H_pre, H_post, s);
+  return launch_coeffs_epilogue(d, proj_ksplit(d), u_raw, sumsq, b, alpha, H_res, H_pre, H_post, s);
+}
+hipError_t run_coeffs_bwd_epilogue(const mhcl_desc &d, const float *u_raw, const float *sumsq,
+                                   const float *b, const float *alpha, const float *g_H_res,
+                                   const float *g_H_pre, const float *g_H_post,
+                                   const BwdTokenBufs &o, hipStream_t s) {
+  if (d.res_mode == MHCL_RES_SUBSET)
+    return launch_coeffs_bwd_subset(d, proj_ksplit(d), u_raw, sumsq, b, alpha, g_H_res, g_H_pre,
+                                    g_H_post, o, s);
+  return launch_coeffs_bwd_epilogue(d, proj_ksplit(d), u_raw, sumsq, b, alpha, g_H_res, g_H_pre,
+                                    g_H_post, o, s);
+}
+
 }  // namespace
 
 extern "C" {
@@ -202,7 +226,7 @@ int mhcl_coeffs(const mhcl_desc *desc, const void *x, const float *W, const floa
   CoeffsWs w(*desc, ws);
   Disarm disarm;
   MHCL_HIP(run_projection(*desc, x, W, w.u_raw, w.sumsq, w.Wp, MHCL_STAGE_FWD_PROJ, s));
-  MHCL_HIP(launch_coeffs_epilogue(*desc, proj_ksplit(*desc), w.u_raw, w.sumsq, b, alpha, H_res, H_pre, H_post, s));
+  MHCL_HIP(run_coeffs_epilogue(*desc, w.u_raw, w.sumsq, b, alpha, H_res, H_pre, H_post, s));
   return MHCL_OK;
 }
 
@@ -227,7 +251,7 @@ int mhcl_logits(const mhcl_desc *desc, const void *x, const float *W, const floa
 
 int mhcl_ds_chain(int32_t n, int32_t L, int64_t T, const float *H, float *colsum, float *l1,
                   float *prod, float *prod_colsum, float *prod_l1, void *stream) {
-  if (n < 1 || n > kMaxN || L < 1 || T < 0) return MHCL_ERR_INVALID_ARG;
+  if (n < 1 || n > kMaxNSubset || L < 1 || T < 0) return MHCL_ERR_INVALID_ARG;
   if (T == 0) return MHCL_OK;
   if (!H || !aligned16(H)) return MHCL_ERR_INVALID_ARG;
   if (!colsum && !l1 && !prod && !prod_colsum && !prod_l1) return MHCL_ERR_INVALID_ARG;
@@ -277,7 +301,7 @@ int mhcl_fwd_coeffs_pre(const mhcl_desc *desc, const void *x, const float *W, co
   CoeffsWs w(*desc, ws);
   Disarm disarm;
   MHCL_HIP(run_projection(*desc, x, W, w.u_raw, w.sumsq, w.Wp, MHCL_STAGE_FWD_PROJ, s));
-  MHCL_HIP(launch_coeffs_epilogue(*desc, proj_ksplit(*desc), w.u_raw, w.sumsq, b, alpha, H_res, H_pre, H_post, s));
+  MHCL_HIP(run_coeffs_epilogue(*desc, w.u_raw, w.sumsq, b, alpha, H_res, H_pre, H_post, s));
   {
     StageBracket br(MHCL_STAGE_FWD_PRE, s);
     MHCL_HIP(launch_pre(*desc, x, H_pre, h, s));
@@ -334,8 +358,8 @@ int mhcl_coeffs_bwd(const mhcl_desc *desc, const void *x, const float *W, const 
   BwdWs w(*desc, ws, false);
   Disarm disarm;
   MHCL_HIP(run_projection(*desc, x, W, w.u_raw, w.sumsq, w.Wp, MHCL_STAGE_BWD_REDUCE, s));
-  MHCL_HIP(launch_coeffs_bwd_epilogue(*desc, proj_ksplit(*desc), w.u_raw, w.sumsq, b, alpha, g_H_res, g_H_pre,
-                                      g_H_post, w.tok, s));
+  MHCL_HIP(run_coeffs_bwd_epilogue(*desc, w.u_raw, w.sumsq, b, alpha, g_H_res, g_H_pre, g_H_post,
+                                   w.tok, s));
   MHCL_HIP(launch_gx_generic(*desc, M, false, x, W, nullptr, nullptr, w.tok, g_x, nullptr, s));
   MHCL_HIP(launch_gw_generic(*desc, M, x, w.tok.vr, w.partials, g_W, s));
   MHCL_HIP(launch_param_sums(*desc, M, w.tok.gz, g_b, g_alpha, w.psum, s));
@@ -380,7 +404,10 @@ int mhcl_bwd_fused(const mhcl_desc *desc, const void *x, const void *y, const fl
         MHCL_HIP(launch_bwd_reduce(*desc, M, x, y, g_xout, g_h, f, s));
       }
     }
-    MHCL_HIP(launch_bwd_epilogue_fast(*desc, b, alpha, f, s));
+    if (desc->res_mode == MHCL_RES_SUBSET)
+      MHCL_HIP(launch_bwd_epilogue_subset_fast(*desc, b, alpha, f, s));
+    else
+      MHCL_HIP(launch_bwd_epilogue_fast(*desc, b, alpha, f, s));
     if (wide) {
       {
         StageBracket br(MHCL_STAGE_BWD_OUT, s);
@@ -398,8 +425,8 @@ int mhcl_bwd_fused(const mhcl_desc *desc, const void *x, const void *y, const fl
   BwdWs w(*desc, ws, true);
   MHCL_HIP(run_projection(*desc, x, W, w.u_raw, w.sumsq, w.Wp, MHCL_STAGE_BWD_REDUCE, s));
   MHCL_HIP(launch_bwd_dots(*desc, x, y, g_xout, g_h, w.gH_res, w.gH_post, w.gH_pre, s));
-  MHCL_HIP(launch_coeffs_bwd_epilogue(*desc, proj_ksplit(*desc), w.u_raw, w.sumsq, b, alpha, w.gH_res, w.gH_pre,
-                                      w.gH_post, w.tok, s));
+  MHCL_HIP(run_coeffs_bwd_epilogue(*desc, w.u_raw, w.sumsq, b, alpha, w.gH_res, w.gH_pre,
+                                   w.gH_post, w.tok, s));
   {
     StageBracket br(MHCL_STAGE_BWD_OUT, s);
     MHCL_HIP(launch_gx_generic(*desc, M, true, x, W, g_xout, g_h, w.tok, g_x, g_y, s));

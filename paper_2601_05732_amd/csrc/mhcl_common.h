@@ -13,7 +13,9 @@
 
 namespace mhcl {
 
-constexpr int kMaxN = 5;
+constexpr int kMaxN = 5;          // full permutation form and Sinkhorn-Knopp form
+constexpr int kMaxNSubset = 8;    // permutation-subset form
+constexpr int kMaxPerm = 128;     // permutations in a subset
 constexpr int kMaxSkIters = 32;
 
 // ------------------------------------------------------------------ bf16

@@ -128,6 +128,9 @@ hipError_t launch_ds_chain(int n, int L, int64_t T, const float *H, float *colsu
     case 3: return go(std::integral_constant<int, 3>{});
     case 4: return go(std::integral_constant<int, 4>{});
     case 5: return go(std::integral_constant<int, 5>{});
+    case 6: return go(std::integral_constant<int, 6>{});
+    case 7: return go(std::integral_constant<int, 7>{});
+    case 8: return go(std::integral_constant<int, 8>{});
   }
   return hipErrorInvalidValue;
 }

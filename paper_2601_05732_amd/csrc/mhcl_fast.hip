@@ -60,7 +60,7 @@ struct ProjCfg {
 #ifndef MHCL_PROJ_TG
 #define MHCL_PROJ_TG 2
 #endif
-  static constexpr int KC = NT == 2 ? MHCL_PROJ_KC : (NT == 9 ? 2 : 4);   // K steps per chunk
+  static constexpr int KC = NT == 2 ? MHCL_PROJ_KC : (NT >= 4 ? 2 : 4);   // K steps per chunk
   static constexpr int TG = NT == 2 ? MHCL_PROJ_TG : 2;        // 16-token A tiles per wave
   static constexpr int kTokens = 64 * TG;                      // tokens per block
   static constexpr int kChunkVec = KC * NT * 2 * 64;           // u32x4 per chunk
@@ -1146,6 +1146,7 @@ __global__ __launch_bounds__(256, 2) void bwd_gw_lds_kernel(
   }
 }
 
+// logit tiles of the full permutation and Sinkhorn-Knopp forms (n <= 5)
 template <typename F>
 hipError_t dispatch_nt(int NT, F &&f) {
   switch (NT) {
@@ -1156,13 +1157,25 @@ hipError_t dispatch_nt(int NT, F &&f) {
   }
   return hipErrorInvalidValue;
 }
+// any count up to 9 (the permutation-subset form): projection only
+template <typename F>
+hipError_t dispatch_nt_proj(int NT, F &&f) {
+  switch (NT) {
+    case 4: return f(std::integral_constant<int, 4>{});
+    case 5: return f(std::integral_constant<int, 5>{});
+    case 6: return f(std::integral_constant<int, 6>{});
+    case 7: return f(std::integral_constant<int, 7>{});
+    case 8: return f(std::integral_constant<int, 8>{});
+  }
+  return dispatch_nt(NT, f);
+}
 
 }  // namespace
 
 bool fast_path_ok(const mhcl_desc &d) {
   if (d.io_dtype != MHCL_BF16 || d.C % 64 != 0) return false;
-  const int NT = logit_tiles(res_logits(d.n, d.res_mode) + 2 * d.n);
-  return NT == 1 || NT == 2 || NT == 3 || NT == 9;
+  const int NT = logit_tiles(res_logits(d) + 2 * d.n);
+  return NT >= 1 && NT <= 9;
 }
 
 size_t packed_w_b_bytes(const mhcl_desc &d, int M) { return packed_b_bytes(d.n * d.C, M); }
@@ -1177,14 +1190,13 @@ hipError_t launch_pack_w_b(const mhcl_desc &d, int M, const float *W, void *Wp, 
 
 int proj_ksplit(const mhcl_desc &d) {
   if (!fast_path_ok(d)) return 1;
-  const int M = res_logits(d.n, d.res_mode) + 2 * d.n;
+  const int M = res_logits(d) + 2 * d.n;
   int kc = 4, tok = 128;
-  switch (logit_tiles(M)) {
-    case 1: kc = ProjCfg<1>::KC; tok = ProjCfg<1>::kTokens; break;
-    case 2: kc = ProjCfg<2>::KC; tok = ProjCfg<2>::kTokens; break;
-    case 3: kc = ProjCfg<3>::KC; tok = ProjCfg<3>::kTokens; break;
-    case 9: kc = ProjCfg<9>::KC; tok = ProjCfg<9>::kTokens; break;
-  }
+  (void)dispatch_nt_proj(logit_tiles(M), [&](auto nt) {
+    kc = ProjCfg<decltype(nt)::value>::KC;
+    tok = ProjCfg<decltype(nt)::value>::kTokens;
+    return hipSuccess;
+  });
   const int nsteps = d.n * d.C / 32;
   const int64_t blocks = (d.T + tok - 1) / tok;
   int ks = 1;   // enough blocks for two per CU, each part a whole number of chunk pairs
@@ -1196,7 +1208,7 @@ hipError_t launch_proj_mfma(const mhcl_desc &d, int M, const void *x, const void
                             float *sumsq, hipStream_t s) {
   const int K = d.n * d.C;
   const int ks = proj_ksplit(d);
-  return dispatch_nt(logit_tiles(M), [&](auto nt) {
+  return dispatch_nt_proj(logit_tiles(M), [&](auto nt) {
     constexpr int NT = decltype(nt)::value;
     auto kern = proj_mfma_kernel<NT>;
     constexpr int lds = ProjCfg<NT>::kLdsBytes;
@@ -1217,12 +1229,14 @@ hipError_t launch_proj_mfma(const mhcl_desc &d, int M, const void *x, const void
 // ---- fused backward, bf16, n <= 4 -------------------------------------------
 // n <= 4 (at most 32 logits): fused passes; n = 5: the wide variant of pass 2
 bool fast_bwd_ok(const mhcl_desc &d) { return fast_path_ok(d); }
-bool fast_bwd_wide(const mhcl_desc &d) { return d.n > 4; }
+// the single-kernel pass 2 exists for the (n, logit tiles) pairs of the full forms with
+// n <= 4; everything else (n >= 5, any permutation subset) takes the wide pass 2
+bool fast_bwd_wide(const mhcl_desc &d) { return d.n > 4 || d.res_mode == MHCL_RES_SUBSET; }
 
 namespace {
 // K steps per wave of bwd_gw_kernel: bounded by its accumulators (2 * NT * 4 registers per step)
 int gw_csw(const mhcl_desc &d) {
-  return logit_tiles(res_logits(d.n, d.res_mode) + 2 * d.n) <= 3 ? 4 : 2;
+  return logit_tiles(res_logits(d) + 2 * d.n) <= 3 ? 4 : 2;
 }
 int gw_xblocks(const mhcl_desc &d) {
   const int per_block = 4 * gw_csw(d);
@@ -1234,7 +1248,7 @@ int out_gw_tokens_per_block(const mhcl_desc &d) {
   // Token chunks: enough of them that (C / 64) x chunks fills the chip about four
   // times over, at least 16, never more than 64 MiB of partial g_W copies, and
   // blocks of a whole number of 64-token iterations (at least 512 tokens).
-  const int64_t M = res_logits(d.n, d.res_mode) + 2 * d.n;
+  const int64_t M = res_logits(d) + 2 * d.n;
   const int64_t copy_bytes = static_cast<int64_t>(d.n) * d.C * M * 4;
   int64_t chunks = (1024 + d.C / 64 - 1) / (d.C / 64);
   if (chunks < 16) chunks = 16;
@@ -1259,8 +1273,8 @@ int gw_chunks_fast(const mhcl_desc &d) {
 FastBwdWs::FastBwdWs(const mhcl_desc &d, void *ws) {
   WsCursor c(ws);
   const size_t T = static_cast<size_t>(d.T), Tpad = (T + 63) / 64 * 64;
-  const int n = d.n, M = res_logits(d.n, d.res_mode) + 2 * d.n, K = d.n * d.C;
-  CP = n <= 4 ? 32 : 40;
+  const int n = d.n, M = res_logits(d) + 2 * d.n, K = d.n * d.C;
+  CP = (n * n + 2 * n + 1 + 7) / 8 * 8;   // H_res | H_pre | H_post | coefx, padded
   MP32 = logit_steps(M) * 32;
   MP16 = logit_tiles(M) * 16;
   parts = fast_bwd_wide(d) ? proj_ksplit(d) : 1;   // the wide path recomputes with proj_mfma_kernel
@@ -1356,7 +1370,7 @@ hipError_t launch_bwd_gw(const mhcl_desc &d, int M, const void *x, const FastBwd
   const int chunks = gw_chunks_fast(d);
   const int bpc = static_cast<int>((nblk + chunks - 1) / chunks);
   float *dst = chunks == 1 ? g_W : w.partials;
-  hipError_t e = dispatch_nt(logit_tiles(M), [&](auto nt) {
+  hipError_t e = dispatch_nt_proj(logit_tiles(M), [&](auto nt) {
     constexpr int NT = decltype(nt)::value;
     if constexpr (NT <= 3) {
       hipLaunchKernelGGL((bwd_gw_kernel<NT, 4>), dim3(gw_xblocks(d), chunks), dim3(256), 0, s,
@@ -1394,16 +1408,32 @@ hipError_t launch_bwd_out_wide(const mhcl_desc &d, int M, const void *x, const v
   switch (MS) {
     case 1: e = wv(std::integral_constant<int, 1>{}); break;
     case 2: e = wv(std::integral_constant<int, 2>{}); break;
+    case 3: e = wv(std::integral_constant<int, 3>{}); break;
+    case 4: e = wv(std::integral_constant<int, 4>{}); break;
     case 5: e = wv(std::integral_constant<int, 5>{}); break;
   }
   if (e != hipSuccess) return e;
-  if (d.n != 5) return hipErrorInvalidValue;
   const int64_t vecs = d.T * (d.C / 8);
-  hipLaunchKernelGGL(mix_wide_kernel<5>, dim3(static_cast<unsigned>((vecs + 255) / 256)), dim3(256),
-                     0, s, static_cast<const uint16_t *>(x), static_cast<const uint16_t *>(g_xout),
-                     static_cast<const uint16_t *>(g_h), w.D, w.cpk, w.CP, d.C, d.T,
-                     static_cast<uint16_t *>(g_x), static_cast<uint16_t *>(g_y));
-  return hipGetLastError();
+  auto mix = [&](auto nn) {
+    constexpr int N = decltype(nn)::value;
+    hipLaunchKernelGGL(mix_wide_kernel<N>, dim3(static_cast<unsigned>((vecs + 255) / 256)),
+                       dim3(256), 0, s, static_cast<const uint16_t *>(x),
+                       static_cast<const uint16_t *>(g_xout), static_cast<const uint16_t *>(g_h),
+                       w.D, w.cpk, w.CP, d.C, d.T, static_cast<uint16_t *>(g_x),
+                       static_cast<uint16_t *>(g_y));
+    return hipGetLastError();
+  };
+  switch (d.n) {
+    case 1: return mix(std::integral_constant<int, 1>{});
+    case 2: return mix(std::integral_constant<int, 2>{});
+    case 3: return mix(std::integral_constant<int, 3>{});
+    case 4: return mix(std::integral_constant<int, 4>{});
+    case 5: return mix(std::integral_constant<int, 5>{});
+    case 6: return mix(std::integral_constant<int, 6>{});
+    case 7: return mix(std::integral_constant<int, 7>{});
+    case 8: return mix(std::integral_constant<int, 8>{});
+  }
+  return hipErrorInvalidValue;
 }
 
 // g_x, g_y and g_W from one pass (n <= 4)

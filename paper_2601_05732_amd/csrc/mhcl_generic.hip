@@ -11,8 +11,9 @@ namespace {
 
 constexpr int kBlock = 256;
 
+// n = 1..5: kernels that unroll the compile-time permutation table
 template <typename F>
-hipError_t dispatch_n(int n, F &&f) {
+hipError_t dispatch_n5(int n, F &&f) {
   switch (n) {
     case 1: return f(std::integral_constant<int, 1>{});
     case 2: return f(std::integral_constant<int, 2>{});
@@ -21,6 +22,16 @@ hipError_t dispatch_n(int n, F &&f) {
     case 5: return f(std::integral_constant<int, 5>{});
   }
   return hipErrorInvalidValue;
+}
+// n = 1..8: the stream kernels (the permutation-subset form goes up to 8)
+template <typename F>
+hipError_t dispatch_n(int n, F &&f) {
+  switch (n) {
+    case 6: return f(std::integral_constant<int, 6>{});
+    case 7: return f(std::integral_constant<int, 7>{});
+    case 8: return f(std::integral_constant<int, 8>{});
+  }
+  return dispatch_n5(n, f);
 }
 template <typename F>
 hipError_t dispatch_io(int io, F &&f) {
@@ -33,7 +44,7 @@ hipError_t dispatch_mode(int mode, F &&f) {
   return f(std::integral_constant<int, MHCL_RES_SK>{});
 }
 
-// Sum over the block of CNT per-thread values (CNT <= 64); the totals land in
+// Sum over the block of CNT per-thread values (CNT <= 256); the totals land in
 // red[0..cnt).  Fixed order: butterfly inside each wave, then waves 0..3.
 template <int CNT>
 __device__ __forceinline__ void block_sum(float (&v)[CNT], float *red /* [4*CNT] */) {
@@ -564,7 +575,7 @@ hipError_t launch_proj_generic(const mhcl_desc &d, int M, const void *x, const f
 hipError_t launch_coeffs_epilogue(const mhcl_desc &d, int parts, const float *u_raw,
                                   const float *sumsq, const float *b, const float *alpha, float *H_res, float *H_pre,
                                   float *H_post, hipStream_t s) {
-  return dispatch_n(d.n, [&](auto nn) {
+  return dispatch_n5(d.n, [&](auto nn) {
     return dispatch_mode(d.res_mode, [&](auto mm) {
       constexpr int N = decltype(nn)::value, MODE = decltype(mm)::value;
       hipLaunchKernelGGL((coeffs_epilogue_kernel<N, MODE>), dim3(blocks_for(d.T, 128)), dim3(128),
@@ -580,7 +591,7 @@ hipError_t launch_coeffs_bwd_epilogue(const mhcl_desc &d, int parts, const float
                                       const float *b, const float *alpha, const float *g_H_res,
                                       const float *g_H_pre, const float *g_H_post,
                                       const BwdTokenBufs &o, hipStream_t s) {
-  return dispatch_n(d.n, [&](auto nn) {
+  return dispatch_n5(d.n, [&](auto nn) {
     return dispatch_mode(d.res_mode, [&](auto mm) {
       constexpr int N = decltype(nn)::value, MODE = decltype(mm)::value;
       hipLaunchKernelGGL((coeffs_bwd_epilogue_kernel<N, MODE>), dim3(blocks_for(d.T, 128)),

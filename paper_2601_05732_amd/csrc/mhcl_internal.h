@@ -9,7 +9,11 @@
 namespace mhcl {
 
 inline int host_factorial(int n) { return n <= 1 ? 1 : n * host_factorial(n - 1); }
-inline int res_logits(int n, int mode) { return mode == MHCL_RES_LITE ? host_factorial(n) : n * n; }
+inline int res_logits(const mhcl_desc &d) {
+  if (d.res_mode == MHCL_RES_LITE) return host_factorial(d.n);
+  if (d.res_mode == MHCL_RES_SUBSET) return d.n_perm;
+  return d.n * d.n;
+}
 inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 
 // Carves a caller-provided workspace into 256-byte aligned pieces.
@@ -78,6 +82,15 @@ hipError_t launch_param_sums(const mhcl_desc &d, int M, const float *gz, float *
 hipError_t launch_param_sums_rows(int64_t rows, int M, const float *src, float *g_b,
                                   float *g_alpha, float *part, hipStream_t s);
 
+// ---- permutation-subset form (run-time table d.perm, n up to 8) --------------
+hipError_t launch_coeffs_subset(const mhcl_desc &d, int parts, const float *u_raw,
+                                const float *sumsq, const float *b, const float *alpha,
+                                float *H_res, float *H_pre, float *H_post, hipStream_t s);
+hipError_t launch_coeffs_bwd_subset(const mhcl_desc &d, int parts, const float *u_raw,
+                                    const float *sumsq, const float *b, const float *alpha,
+                                    const float *g_H_res, const float *g_H_pre,
+                                    const float *g_H_post, const BwdTokenBufs &o, hipStream_t s);
+
 // ---- diagnostics ----------------------------------------------------------
 // z [T,M] and spread [T] (max - min of the residual logits); either may be null
 hipError_t launch_logits(const mhcl_desc &d, int M, int parts, const float *u_raw,
@@ -99,7 +112,7 @@ hipError_t launch_proj_mfma(const mhcl_desc &d, int M, const void *x, const void
 
 // fused backward on the fast path (needs fast_bwd_ok(desc))
 bool fast_bwd_ok(const mhcl_desc &d);
-bool fast_bwd_wide(const mhcl_desc &d);   // n = 5: pass 2 split into W vr and the mixing
+bool fast_bwd_wide(const mhcl_desc &d);   // n >= 5 or a subset: pass 2 split into W vr and the mixing
 int gw_chunks_fast(const mhcl_desc &d);
 struct FastBwdWs {
   // gz: [ceil(T/64)][M+3] sums of g_z and g_z u over each 64 tokens
@@ -116,6 +129,9 @@ hipError_t launch_bwd_reduce(const mhcl_desc &d, int M, const void *x, const voi
                              hipStream_t s);
 hipError_t launch_bwd_epilogue_fast(const mhcl_desc &d, const float *b, const float *alpha,
                                     const FastBwdWs &w, hipStream_t s);
+// the same stage for the permutation-subset form (run-time table)
+hipError_t launch_bwd_epilogue_subset_fast(const mhcl_desc &d, const float *b, const float *alpha,
+                                           const FastBwdWs &w, hipStream_t s);
 hipError_t launch_bwd_out_wide(const mhcl_desc &d, int M, const void *x, const void *g_xout,
                                const void *g_h, const FastBwdWs &w, void *g_x, void *g_y,
                                hipStream_t s);

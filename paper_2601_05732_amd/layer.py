@@ -9,12 +9,14 @@ import torch
 from . import binding as mhcl
 
 
-def desc_for(wl, T=None) -> mhcl.Desc:
-    """Descriptor for a workload record (fields n, C, T, io, res_mode, sk_iters, eps)."""
+def desc_for(wl, T=None, perm=None) -> mhcl.Desc:
+    """Descriptor for a workload record (fields n, C, T, io, res_mode, sk_iters, eps);
+    `perm` is the int8 GPU tensor [K, n] of the permutation-subset form."""
+    mode = {"lite": mhcl.RES_LITE, "sk": mhcl.RES_SK, "subset": mhcl.RES_SUBSET}[wl.res_mode]
+    if (mode == mhcl.RES_SUBSET) != (perm is not None):
+        raise ValueError("perm goes with res_mode 'subset', and only with it")
     return mhcl.Desc(wl.n, wl.C, wl.T if T is None else T,
-                     mhcl.BF16 if wl.io == "bf16" else mhcl.F32,
-                     mhcl.RES_LITE if wl.res_mode == "lite" else mhcl.RES_SK,
-                     wl.sk_iters, wl.eps)
+                     mhcl.BF16 if wl.io == "bf16" else mhcl.F32, mode, wl.sk_iters, wl.eps, perm)
 
 
 class GpuLayer:

@@ -37,16 +37,19 @@ class Workload:
     T: int
     io: str = "bf16"          # "bf16" | "f32": dtype of every stream tensor
     b_std: float = 0.1
-    res_mode: str = "lite"    # "lite" | "sk"
+    res_mode: str = "lite"    # "lite" | "sk" | "subset"
     sk_iters: int = 20
     eps: float = 1e-6
     alpha: tuple = (1.0, 1.0, 1.0)
     backward: bool = True
+    n_perm: int = 0           # "subset": number of permutations kept
 
     @property
     def M(self) -> int:
         if self.res_mode == "lite":
             return math.factorial(self.n) + 2 * self.n
+        if self.res_mode == "subset":
+            return self.n_perm + 2 * self.n
         return self.n * self.n + 2 * self.n
 
     @property
@@ -68,6 +71,8 @@ WORKLOADS = {
     "paper_s_c512": Workload("paper_s_c512", n=4, C=512, T=16384),
     "paper_m_c768": Workload("paper_m_c768", n=4, C=768, T=16384),
     "paper_l_c1024": Workload("paper_l_c1024", n=4, C=1024, T=16384),
+    # Larger n with a subset of the permutations (Sec. 5): 8 streams, 64 of the 8! matrices.
+    "n8_c1024_k64": Workload("n8_c1024_k64", n=8, C=1024, T=16384, res_mode="subset", n_perm=64),
 }
 
 
@@ -95,6 +100,21 @@ def _randn(shape, gen, device, dtype, std=1.0, chunk_rows=4096):
     return out
 
 
+def subset_permutations(n: int, K: int, seed: int = 0) -> np.ndarray:
+    """K distinct permutations of 0..n-1, the identity first, the rest drawn
+    uniformly (Sec. 5: "sampling a subset of permutation matrices"), int8 [K, n]."""
+    assert 1 <= K <= math.factorial(n)
+    rng = np.random.default_rng(seed)
+    rows = [tuple(range(n))]
+    seen = set(rows)
+    while len(rows) < K:
+        p = tuple(rng.permutation(n).tolist())
+        if p not in seen:
+            seen.add(p)
+            rows.append(p)
+    return np.array(rows, dtype=np.int8)
+
+
 def make_inputs(wl: Workload, seed: int = 0, device: str = "cpu") -> dict:
     """Draw x, W, b, alpha, y, g_xout, g_h for `wl`, in that order, from one
     generator seeded with `seed` on `device`.
@@ -118,6 +138,8 @@ def make_inputs(wl: Workload, seed: int = 0, device: str = "cpu") -> dict:
     if wl.backward:
         d["g_xout"] = _randn((T, n, C), gen, device, sd)
         d["g_h"] = _randn((T, C), gen, device, sd)
+    if wl.res_mode == "subset":
+        d["perm"] = torch.from_numpy(subset_permutations(n, wl.n_perm, seed)).to(device)
     return d
 
 

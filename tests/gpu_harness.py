@@ -30,7 +30,9 @@ def oracle_reference(inp: dict, wl: si.Workload, tokens=None, backward=True):
     sel = (lambda t: t) if tokens is None else (lambda t: t[torch.as_tensor(tokens, device=t.device)])
     x, y = to_np64(sel(inp["x"])), to_np64(sel(inp["y"]))
     W, b, al = to_np64(inp["W"]), to_np64(inp["b"]), to_np64(inp["alpha"])
+    sigma = inp["perm"].cpu().numpy().astype(np.int32) if wl.res_mode == "subset" else None
     if not backward:
-        return oracle.forward(x, W, b, al, y, eps=wl.eps, res_mode=wl.res_mode, iters=wl.sk_iters)
+        return oracle.forward(x, W, b, al, y, eps=wl.eps, res_mode=wl.res_mode, iters=wl.sk_iters,
+                              sigma=sigma)
     return oracle.backward(x, W, b, al, y, to_np64(sel(inp["g_xout"])), to_np64(sel(inp["g_h"])),
-                           eps=wl.eps, res_mode=wl.res_mode, iters=wl.sk_iters)
+                           eps=wl.eps, res_mode=wl.res_mode, iters=wl.sk_iters, sigma=sigma)

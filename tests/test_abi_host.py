@@ -77,7 +77,7 @@ def test_null_and_misaligned_pointers_fail_before_any_launch():
     assert L.mhcl_logits(ctypes.byref(d.c), ok, ok, ok, ok, ok, None, None, 0, None) == 3
     assert L.mhcl_ds_chain(4, 2, 16, None, ok, ok, ok, ok, ok, None) == 1
     assert L.mhcl_ds_chain(4, 2, 16, ok, None, None, None, None, None, None) == 1
-    assert L.mhcl_ds_chain(6, 2, 16, ok, ok, ok, ok, ok, ok, None) == 1
+    assert L.mhcl_ds_chain(9, 2, 16, ok, ok, ok, ok, ok, ok, None) == 1
     assert L.mhcl_ds_chain(4, 0, 16, ok, ok, ok, ok, ok, ok, None) == 1
     assert L.mhcl_ds_chain(4, 2, 16, ok, ok + 4, ok, ok, ok, ok, None) == 1
     assert L.mhcl_ds_chain(4, 2, 0, None, None, None, None, None, None, None) == 0
@@ -89,3 +89,20 @@ def test_binding_refuses_cpu_tensors():
     x = torch.zeros(4, 2, 8)
     with pytest.raises(ValueError):
         mhcl.mhcl_pre(d, x, torch.zeros(4, 2), torch.zeros(4, 8))
+
+
+def test_subset_descriptor_fields_are_validated_on_the_host():
+    class FakePerm:                      # any non-null address: validation never dereferences it
+        pass
+    d = mhcl.Desc(6, 64, 16, mhcl.BF16, mhcl.RES_SUBSET)
+    assert mhcl.lib().mhcl_validate(ctypes.byref(d.c)) == 1          # no table
+    d.c.n_perm, d.c.perm = 12, 4096
+    assert mhcl.lib().mhcl_validate(ctypes.byref(d.c)) == 0
+    assert mhcl.lib().mhcl_logit_count(ctypes.byref(d.c)) == 12 + 12
+    assert mhcl.lib().mhcl_workspace_bytes(ctypes.byref(d.c), mhcl.OP_BWD_FUSED) > 0
+    d.c.n_perm = 129
+    assert mhcl.lib().mhcl_validate(ctypes.byref(d.c)) == 1
+    d.c.n_perm, d.c.n = 12, 9
+    assert mhcl.lib().mhcl_validate(ctypes.byref(d.c)) == 1
+    full = mhcl.Desc(6, 64, 16)                                      # n = 6 only in the subset form
+    assert mhcl.lib().mhcl_validate(ctypes.byref(full.c)) == 1

@@ -37,7 +37,7 @@ def _check_forward(L, ref, wl, tokens=None):
         got = sel(to_np64(getattr(L, name)))
         e = rel_err(got, ref[name])
         assert e <= tol, f"{name}: {e:.3e} > {tol}"
-    if wl.res_mode == "lite":
+    if wl.res_mode in ("lite", "subset"):
         H = to_np64(L.H_res)
         assert np.abs(H.sum(axis=1) - 1).max() <= 1e-6 and np.abs(H.sum(axis=2) - 1).max() <= 1e-6
         assert H.min() >= 0.0
