@@ -118,16 +118,24 @@ def cpu_baseline(inp, wl, sample_tokens):
     import oracle
     f64 = lambda t: t[:sample_tokens].detach().to("cpu", torch.float64).numpy()
     full = lambda t: t.detach().to("cpu", torch.float64).numpy()
-    x, y, gxo, gh = f64(inp["x"]), f64(inp["y"]), f64(inp["g_xout"]), f64(inp["g_h"])
+    x, y = f64(inp["x"]), f64(inp["y"])
     W, b, al = full(inp["W"]), full(inp["b"]), full(inp["alpha"])
-    oracle.backward(x[:8], W, b, al, y[:8], gxo[:8], gh[:8], eps=wl.eps, res_mode=wl.res_mode,
-                    iters=wl.sk_iters)   # loads the library, warms the caches
+    kw = dict(eps=wl.eps, res_mode=wl.res_mode, iters=wl.sk_iters)
+    if wl.res_mode == "subset":
+        kw["sigma"] = inp["perm"].cpu().numpy().astype(np.int32)
+    if wl.backward:
+        gxo, gh = f64(inp["g_xout"]), f64(inp["g_h"])
+        run = lambda k: oracle.backward(x[:k], W, b, al, y[:k], gxo[:k], gh[:k], **kw)
+    else:
+        run = lambda k: oracle.forward(x[:k], W, b, al, y[:k], **kw)
+    run(8)                               # loads the library, warms the caches
     t0 = time.perf_counter()
-    oracle.backward(x, W, b, al, y, gxo, gh, eps=wl.eps, res_mode=wl.res_mode, iters=wl.sk_iters)
+    run(sample_tokens)
     dt = time.perf_counter() - t0
     cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
     return {"value": sample_tokens / dt, "unit": "tokens/s", "cores": cores, "kind": "oracle",
-            "sample": f"first {sample_tokens} of {wl.T} tokens, forward+backward, fp64, "
+            "sample": f"first {sample_tokens} of {wl.T} tokens, "
+                      f"{'forward+backward' if wl.backward else 'forward'}, fp64, "
                       f"{dt:.1f} s"}
 
 
@@ -161,8 +169,7 @@ def main():
     wl = si.WORKLOADS[args.workload]
     torch.cuda.set_device(0)
     inp = si.make_inputs(wl, seed=0, device="cuda:0")
-    if not wl.backward:
-        raise SystemExit("bench.py times forward+backward; pick a workload with backward")
+    fwd_only = not wl.backward      # a forward-only workload times the two forward calls alone
     d = mhcl.desc_for(wl, perm=inp.get("perm"))
     L = mhcl.GpuLayer(d, inp)
     e = 2 if wl.io == "bf16" else 4
@@ -179,6 +186,8 @@ def main():
                                  L.H_post, L.h, L.ws)
         arm(stage == 3)
         mhcl.mhcl_post(dd, i["x"], i["y"], L.H_res, L.H_post, L.x_out)
+        if fwd_only:
+            return
         arm(stage in (4, 5, 6))
         mhcl.mhcl_bwd_fused(dd, i["x"], i["y"], i["W"], i["b"], i["alpha"], i["g_xout"], i["g_h"],
                             L.g_x, L.g_y, L.g_W, L.g_b, L.g_alpha, L.ws)
@@ -211,6 +220,8 @@ def main():
         step()
     stage_ms = {}
     for i, st in enumerate(STAGES):
+        if fwd_only and st > 3:
+            continue
         step(st, probe, 2 * i)
         torch.cuda.synchronize()
         try:
@@ -250,11 +261,12 @@ def main():
 
     ms_per_step = dt / args.steps * 1e3
     tokens_per_s = wl.T / (dt / args.steps)
-    floor_bytes = ((3 * wl.n + 2) + (3 * wl.n + 3)) * wl.C * e * wl.T
+    floor_bytes = ((3 * wl.n + 2) + (0 if fwd_only else 3 * wl.n + 3)) * wl.C * e * wl.T
     achieved = stage_bytes(dominant, wl.n, wl.C, wl.T, e) / kern_ms / 1e6
     out = {
         "metric": "tokens/s + achieved HBM GB/s, fused mHC-lite fwd+bwd, n=4 C=4096 32k tok"
-                  if args.workload == "n4_c4096" else f"tokens/s, fused fwd+bwd, {args.workload}",
+                  if args.workload == "n4_c4096" else
+                  f"tokens/s, {'forward' if fwd_only else 'fused fwd+bwd'}, {args.workload}",
         "value": tokens_per_s,
         "unit": "tokens/s",
         "n_gpus": 1,
@@ -268,7 +280,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{args.workload}: n={wl.n} C={wl.C} T={wl.T} "
                                f"{wl.io} streams, fp32 accumulate, {wl.res_mode} H_res, "
-                               "forward (coeffs+pre, post) + fused backward"
+                               "forward (coeffs+pre, post)" + ("" if fwd_only else " + fused backward")
                                + (", HIP graph replay" if args.graph else ""),
                    "path_hbm_gbs_algorithmic": floor_bytes / (dt / args.steps) / 1e9,
                    "path_frac_of_peak": floor_bytes / (dt / args.steps) / 1e9 / PEAK_HBM_GBS},

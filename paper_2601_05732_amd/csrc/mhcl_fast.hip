@@ -537,8 +537,8 @@ __global__ __launch_bounds__(64) void bwd_epilogue_fast_kernel(
 // with x^T obtained by an MFMA against a 0/1 selection matrix (exact) as in
 // bwd_gw_kernel.  Accumulators stay in registers over the block's token chunk;
 // partial sums per chunk go to `gw_part` and are added in chunk order.
-template <int N, int NT>
-__global__ __launch_bounds__(256, 2) void bwd_out_gw_kernel(
+template <int N, int NT, int SLABS>
+__global__ __launch_bounds__(256 * SLABS, SLABS == 1 ? 2 : 1) void bwd_out_gw_kernel(
     const uint16_t *__restrict__ x, const uint16_t *__restrict__ g,
     const uint16_t *__restrict__ gh, const u32x4 *__restrict__ Wa, const float *__restrict__ cpk,
     const uint16_t *__restrict__ vr_hi, const uint16_t *__restrict__ vr_lo,
@@ -548,14 +548,17 @@ __global__ __launch_bounds__(256, 2) void bwd_out_gw_kernel(
   constexpr int NCP = N * N + 2 * N + 1;
   constexpr int NCP4 = (NCP + 3) / 4;
   constexpr int kSliceVec = N * 4 * 2 * 64;   // 16-byte words of W per 64-column step
-  extern __shared__ u32x4 lds[];
+  // SLABS adjacent 64-column steps per block, four waves each, all on the same tokens at
+  // the same time: a row visit of the block then covers SLABS x 128 contiguous bytes
+  extern __shared__ u32x4 lds_all[];
+  const int lane = threadIdx.x & 63, wave = (threadIdx.x >> 6) & 3, slab = threadIdx.x >> 8;
+  u32x4 *lds = lds_all + slab * (2 * kSliceVec);
   u32x4 *xch = lds + kSliceVec;               // x tiles of one iteration: [stream][wave][u][lane]
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int r = lane & 15, q = lane >> 4;
-  const int S = blockIdx.x;
+  const int S = blockIdx.x * SLABS + slab;
   const int c0 = S * 64 + q * 8;
   const int nS = C / 64;
-  for (int e = threadIdx.x; e < kSliceVec; e += 256) {
+  for (int e = threadIdx.x & 255; e < kSliceVec; e += 256) {
     const int j = e / 512, rem = e % 512;
     lds[e] = Wa[static_cast<size_t>(j * nS + S) * 512 + rem];
   }
@@ -1444,15 +1447,27 @@ hipError_t launch_bwd_out_gw(const mhcl_desc &d, int M, const void *x, const voi
   const int tpb = out_gw_tokens_per_block(d);
   const int chunks = static_cast<int>((d.T + tpb - 1) / tpb);
   float *dst = chunks == 1 ? g_W : w.partials;
+  // two adjacent 64-column steps per block where C allows it
+  const bool pair = (d.C / 64) % 2 == 0;
   auto go = [&](auto nn, auto nt) {
     constexpr int N = decltype(nn)::value, NT = decltype(nt)::value;
     constexpr int lds = (N * 4 * 2 * 64) * 2 * 16;
-    hipLaunchKernelGGL((bwd_out_gw_kernel<N, NT>), dim3(d.C / 64, chunks), dim3(256), lds, s,
-                       static_cast<const uint16_t *>(x), static_cast<const uint16_t *>(g_xout),
-                       static_cast<const uint16_t *>(g_h), reinterpret_cast<const u32x4 *>(w.Wa),
-                       w.cpk, w.vr_hi, w.vr_lo, w.vrT_hi, w.vrT_lo, w.MP16, M, d.C, d.T, tpb, w.CP,
-                       static_cast<uint16_t *>(g_x), static_cast<uint16_t *>(g_y), dst);
-    return hipGetLastError();
+    auto launch = [&](auto sl) {
+      constexpr int SL = decltype(sl)::value;
+      auto kern = bwd_out_gw_kernel<N, NT, SL>;
+      if (lds * SL > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds * SL);
+        if (e != hipSuccess) return e;
+      }
+      hipLaunchKernelGGL(kern, dim3(d.C / 64 / SL, chunks), dim3(256 * SL), lds * SL, s,
+                         static_cast<const uint16_t *>(x), static_cast<const uint16_t *>(g_xout),
+                         static_cast<const uint16_t *>(g_h), reinterpret_cast<const u32x4 *>(w.Wa),
+                         w.cpk, w.vr_hi, w.vr_lo, w.vrT_hi, w.vrT_lo, w.MP16, M, d.C, d.T, tpb,
+                         w.CP, static_cast<uint16_t *>(g_x), static_cast<uint16_t *>(g_y), dst);
+      return hipGetLastError();
+    };
+    return pair ? launch(std::integral_constant<int, 2>{}) : launch(std::integral_constant<int, 1>{});
   };
   using I1 = std::integral_constant<int, 1>;
   using I2 = std::integral_constant<int, 2>;
