@@ -1248,17 +1248,21 @@ int gw_xblocks(const mhcl_desc &d) {
 }  // namespace
 
 int out_gw_tokens_per_block(const mhcl_desc &d) {
-  // Token chunks: enough of them that (C / 64) x chunks fills the chip about four
-  // times over, at least 16, never more than 64 MiB of partial g_W copies, and
-  // blocks of a whole number of 64-token iterations (at least 512 tokens).
+  // Token chunks: as many as make the grid one round of resident blocks (all blocks
+  // then start together and the blocks of a chunk walk down the same rows side by
+  // side), never more than 64 MiB of partial g_W copies, and blocks of a whole
+  // number of 64-token iterations (at least 256 tokens, to amortise staging W).
   const int64_t M = res_logits(d) + 2 * d.n;
   const int64_t copy_bytes = static_cast<int64_t>(d.n) * d.C * M * 4;
-  int64_t chunks = (1024 + d.C / 64 - 1) / (d.C / 64);
-  if (chunks < 16) chunks = 16;
+  const bool pair = (d.C / 64) % 2 == 0;            // two 64-column steps per block
+  const int64_t resident = pair ? 256 : 512;        // blocks the chip holds at once
+  const int64_t xblocks = pair ? d.C / 128 : d.C / 64;
+  int64_t chunks = resident / xblocks;
+  if (chunks < 1) chunks = 1;
   const int64_t cap = (64ll << 20) / copy_bytes;
   if (chunks > cap) chunks = cap < 1 ? 1 : cap;
   int64_t tpb = ((d.T + chunks - 1) / chunks + 63) / 64 * 64;
-  if (tpb < 512) tpb = 512;
+  if (tpb < 256) tpb = 256;
   return static_cast<int>(tpb);
 }
 
