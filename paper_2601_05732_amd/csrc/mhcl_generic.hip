@@ -482,14 +482,23 @@ __global__ __launch_bounds__(kBlock) void gw_generic_kernel(const void *__restri
   }
 }
 
+// out[i] = sum over chunks of part[c][i], in a fixed association: the four waves of a
+// block each add every fourth chunk for the same 64 elements (several independent
+// loads in flight), then ((s0 + s1) + s2) + s3.
 __global__ __launch_bounds__(kBlock) void sum_partials_kernel(const float *__restrict__ part,
                                                               size_t size, int chunks,
                                                               float *__restrict__ out) {
-  const size_t i = static_cast<size_t>(blockIdx.x) * kBlock + threadIdx.x;
-  if (i >= size) return;
+  __shared__ float red[4][64];
+  const int el = threadIdx.x & 63, grp = threadIdx.x >> 6;
+  const size_t i = static_cast<size_t>(blockIdx.x) * 64 + el;
   float s = 0.f;
-  for (int c = 0; c < chunks; ++c) s += part[c * size + i];
-  out[i] = s;
+  if (i < size) {
+#pragma unroll 4
+    for (int c = grp; c < chunks; c += 4) s += part[c * size + i];
+  }
+  red[grp][el] = s;
+  __syncthreads();
+  if (grp == 0 && i < size) out[i] = ((red[0][el] + red[1][el]) + red[2][el]) + red[3][el];
 }
 
 // Column sums of a [T, ld] matrix in two fixed-order stages.  Stage 1: block b
@@ -725,7 +734,7 @@ hipError_t launch_gw_generic(const mhcl_desc &d, int M, const void *x, const flo
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || chunks == 1) return e;
     const size_t size = static_cast<size_t>(nC) * M;
-    hipLaunchKernelGGL(sum_partials_kernel, dim3(blocks_for(size, kBlock)), dim3(kBlock), 0, s,
+    hipLaunchKernelGGL(sum_partials_kernel, dim3(blocks_for(size, 64)), dim3(kBlock), 0, s,
                        (const float *)partials, size, chunks, g_W);
     return hipGetLastError();
   });
@@ -733,7 +742,7 @@ hipError_t launch_gw_generic(const mhcl_desc &d, int M, const void *x, const flo
 
 hipError_t launch_sum_partials(const float *partials, size_t size, int chunks, float *out,
                                hipStream_t s) {
-  hipLaunchKernelGGL(sum_partials_kernel, dim3(blocks_for(size, kBlock)), dim3(kBlock), 0, s,
+  hipLaunchKernelGGL(sum_partials_kernel, dim3(blocks_for(size, 64)), dim3(kBlock), 0, s,
                      partials, size, chunks, out);
   return hipGetLastError();
 }
@@ -757,7 +766,7 @@ hipError_t launch_fill_zero(float *p, size_t count, hipStream_t s) {
 hipError_t launch_param_sums_rows(int64_t rows, int M, const float *src, float *g_b,
                                   float *g_alpha, float *part, hipStream_t s) {
   const int ld = M + 3;
-  int64_t nb = (rows + 127) / 128;
+  int64_t nb = (rows + 15) / 16;     // short per-thread chains; stage 2 adds at most 256 rows
   if (nb > 256) nb = 256;
   if (nb < 1) nb = 1;
   const int nblocks = static_cast<int>(nb);
@@ -776,8 +785,9 @@ hipError_t launch_param_sums(const mhcl_desc &d, int M, const float *gz, float *
   return launch_param_sums_rows(d.T, M, gz, g_b, g_alpha, part, s);
 }
 
+// upper bound of the stage-1 block count of launch_param_sums_rows for any rows <= T
 int param_sum_blocks(const mhcl_desc &d) {
-  int64_t b = (d.T + 127) / 128;
+  int64_t b = (d.T + 15) / 16;
   if (b > 256) b = 256;
   if (b < 1) b = 1;
   return static_cast<int>(b);
