@@ -832,6 +832,146 @@ __global__ __launch_bounds__(256, 2) void wv_kernel(const u32x4 *__restrict__ Wa
   }
 }
 
+// Pass 2 of the wide case in one kernel, for slices that fit on chip when only the
+// leading bf16 part of W is kept (n = 5: 100 KiB per 64-column step):
+//   g_x[j] = sum_i H_res[i][j] g_xout[i] + H_pre[j] g_h + (W_hi vr)[j] - x[j] coefx
+//   g_y    = sum_i H_post[i] g_xout[i]
+// vr keeps both of its parts.  Rounding W to bf16 in this one product changes
+// (W vr) by about 2^-9 / sqrt(3) of its size, less than the rounding of g_x to bf16
+// that follows.  Nothing is written between the passes (the two-kernel variant
+// stores W vr as fp32 [T, nC] and reads it back).  One block of eight waves per CU,
+// each wave 16 tokens per iteration; lane ownership as in bwd_out_gw_kernel.
+template <int N, int MS>
+__global__ __launch_bounds__(512, 1) void bwd_out_whi_kernel(
+    const uint16_t *__restrict__ x, const uint16_t *__restrict__ g,
+    const uint16_t *__restrict__ gh, const u32x4 *__restrict__ Wa, const float *__restrict__ cpk,
+    const uint16_t *__restrict__ vr_hi, const uint16_t *__restrict__ vr_lo, int MP32, int C,
+    int64_t T, int tokens_per_block, int CP, uint16_t *__restrict__ g_x,
+    uint16_t *__restrict__ g_y) {
+  constexpr int NCP = N * N + 2 * N + 1;
+  constexpr int NCP4 = (NCP + 3) / 4;
+  constexpr int kStreamVec = 4 * MS * 64;       // 16-byte words of W_hi per stream and 64-column step
+  extern __shared__ u32x4 lds[];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int r = lane & 15, q = lane >> 4;
+  const int S = blockIdx.x;
+  const int c0 = S * 64 + q * 8;
+  const int nS = C / 64;
+  for (int e = threadIdx.x; e < N * kStreamVec; e += 512) {
+    const int j = e / kStreamVec, rem = e % kStreamVec;
+    const int blk = rem >> 6, ln = rem & 63;     // blk = h * MS + ms of step j nS + S
+    lds[e] = Wa[((static_cast<size_t>(j * nS + S) * 4 * MS + blk) * 2 + 0) * 64 + ln];
+  }
+  __syncthreads();
+  const u32x4 *wl = lds + lane;
+
+  const int64_t tb = static_cast<int64_t>(blockIdx.y) * tokens_per_block;   // multiple of 128
+  int64_t te = tb + tokens_per_block;
+  if (te > T) te = T;
+
+  auto unpack = [](const u32x4 &v, float (&o)[8]) {
+    o[0] = bf16lo(v.x); o[1] = bf16hi(v.x); o[2] = bf16lo(v.y); o[3] = bf16hi(v.y);
+    o[4] = bf16lo(v.z); o[5] = bf16hi(v.z); o[6] = bf16lo(v.w); o[7] = bf16hi(v.w);
+  };
+  auto pack = [](const float (&o)[8]) {
+    u32x4 v;
+    v.x = cvt_pk_bf16(o[0], o[1]); v.y = cvt_pk_bf16(o[2], o[3]);
+    v.z = cvt_pk_bf16(o[4], o[5]); v.w = cvt_pk_bf16(o[6], o[7]);
+    return v;
+  };
+
+  for (int64_t t0 = tb + wave * 16; t0 < te; t0 += 128) {
+    const int64_t t = t0 + r;
+    const bool live = t < te;
+    const int64_t tl = live ? t : te - 1;
+    u32x4 X[N][2], G[N][2], H[2], vbh[MS], vbl[MS];
+    float4 cp4[NCP4];
+#pragma unroll
+    for (int j = 0; j < N; ++j)
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        G[j][u] = *reinterpret_cast<const u32x4 *>(g + (tl * N + j) * C + c0 + u * 32);
+        X[j][u] = *reinterpret_cast<const u32x4 *>(x + (tl * N + j) * C + c0 + u * 32);
+      }
+#pragma unroll
+    for (int u = 0; u < 2; ++u) H[u] = *reinterpret_cast<const u32x4 *>(gh + tl * C + c0 + u * 32);
+#pragma unroll
+    for (int ms = 0; ms < MS; ++ms) {
+      vbh[ms] = *reinterpret_cast<const u32x4 *>(vr_hi + tl * MP32 + ms * 32 + q * 8);
+      vbl[ms] = *reinterpret_cast<const u32x4 *>(vr_lo + tl * MP32 + ms * 32 + q * 8);
+    }
+    const float4 *cpp = reinterpret_cast<const float4 *>(cpk + tl * CP);
+#pragma unroll
+    for (int e = 0; e < NCP4; ++e) cp4[e] = cpp[e];
+    float cp[NCP4 * 4];
+#pragma unroll
+    for (int e = 0; e < NCP4; ++e) {
+      cp[4 * e] = cp4[e].x; cp[4 * e + 1] = cp4[e].y; cp[4 * e + 2] = cp4[e].z; cp[4 * e + 3] = cp4[e].w;
+    }
+    const float cx = cp[N * N + 2 * N];
+    // Stream by stream, both 64-byte halves of a line computed and stored together; the
+    // g_xout and g_h tiles stay packed and are unpacked at each use (registers).
+    {   // g_y
+      u32x4 ov[2];
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        float o[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] = 0.f;
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+          float gv[8];
+          unpack(G[i][u], gv);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) o[e] += cp[N * N + N + i] * gv[e];
+        }
+        ov[u] = pack(o);
+      }
+      if (live) {
+        *reinterpret_cast<u32x4 *>(g_y + t * C + c0) = ov[0];
+        *reinterpret_cast<u32x4 *>(g_y + t * C + c0 + 32) = ov[1];
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < N; ++j) {
+      u32x4 ov[2];
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        f32x4 wv[2];
+#pragma unroll
+        for (int hh = 0; hh < 2; ++hh) {
+          const int h = 2 * u + hh;
+          wv[hh] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int ms = 0; ms < MS; ++ms) {
+            const u32x4 wh = wl[((j * 4 + h) * MS + ms) * 64];
+            wv[hh] = mfma16(wh, vbh[ms], wv[hh]);
+            wv[hh] = mfma16(wh, vbl[ms], wv[hh]);
+          }
+        }
+        float xv[8], hv[8], o[8];
+        unpack(X[j][u], xv);
+        unpack(H[u], hv);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] = wv[e >> 2][e & 3] - xv[e] * cx + cp[N * N + j] * hv[e];
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+          float gv[8];
+          unpack(G[i][u], gv);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) o[e] += cp[i * N + j] * gv[e];
+        }
+        ov[u] = pack(o);
+      }
+      if (live) {
+        *reinterpret_cast<u32x4 *>(g_x + (t * N + j) * C + c0) = ov[0];
+        *reinterpret_cast<u32x4 *>(g_x + (t * N + j) * C + c0 + 32) = ov[1];
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+}
+
 // Then the stream outputs in row order (one thread per 8 columns of a token):
 //   g_x[j] = sum_i H_res[i][j] g_xout[i] + H_pre[j] g_h + D[j] - x[j] coefx
 //   g_y    = sum_i H_post[i] g_xout[i]
@@ -1399,6 +1539,33 @@ hipError_t launch_bwd_out_wide(const mhcl_desc &d, int M, const void *x, const v
                                const void *g_h, const FastBwdWs &w, void *g_x, void *g_y,
                                hipStream_t s) {
   const int K = d.n * d.C, MS = logit_steps(M);
+  if (d.n == 5 && (MS == 2 || MS == 5)) {
+    // one kernel, W's leading bf16 part resident in LDS; one round of one block per CU
+    const int64_t xb = d.C / 64;
+    int64_t chunks = 256 / xb;
+    if (chunks < 1) chunks = 1;
+    int64_t tpb1 = ((d.T + chunks - 1) / chunks + 127) / 128 * 128;
+    if (tpb1 < 256) tpb1 = 256;
+    while ((d.T + tpb1 - 1) / tpb1 > 32768) tpb1 *= 2;
+    const dim3 grid1(static_cast<unsigned>(xb), static_cast<unsigned>((d.T + tpb1 - 1) / tpb1));
+    auto fused = [&](auto ms) {
+      constexpr int kMS = decltype(ms)::value;
+      constexpr int lds = 5 * 4 * kMS * 64 * 16;
+      auto kern = bwd_out_whi_kernel<5, kMS>;
+      if (lds > 64 * 1024) {
+        hipError_t e1 = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        if (e1 != hipSuccess) return e1;
+      }
+      hipLaunchKernelGGL(kern, grid1, dim3(512), lds, s, static_cast<const uint16_t *>(x),
+                         static_cast<const uint16_t *>(g_xout), static_cast<const uint16_t *>(g_h),
+                         reinterpret_cast<const u32x4 *>(w.Wa), w.cpk, w.vr_hi, w.vr_lo, w.MP32, d.C,
+                         d.T, static_cast<int>(tpb1), w.CP, static_cast<uint16_t *>(g_x),
+                         static_cast<uint16_t *>(g_y));
+      return hipGetLastError();
+    };
+    return MS == 2 ? fused(std::integral_constant<int, 2>{}) : fused(std::integral_constant<int, 5>{});
+  }
   // 1024 tokens per block, more once that would exceed the grid's second dimension
   int64_t tpb = 1024;
   while ((d.T + tpb - 1) / tpb > 32768) tpb *= 2;
