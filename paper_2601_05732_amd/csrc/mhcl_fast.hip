@@ -246,6 +246,28 @@ __global__ __launch_bounds__(256) void pack_w_a_kernel(const float *__restrict__
   Wa[(static_cast<size_t>(blk) * 2 + 1) * 64 + lane] = vl;
 }
 
+// W [K, M] fp32 -> A layout with ONE fp16 part per block (11 significant bits): for the
+// single-kernel wide pass 2, whose LDS holds one part only.  Block index (S*4 + h)*MS + ms.
+__global__ __launch_bounds__(256) void pack_w_a16_kernel(const float *__restrict__ W, int K, int M,
+                                                         int MS, uint4 *__restrict__ Wa) {
+  const int idx = blockIdx.x * 256 + threadIdx.x;
+  const int lane = idx & 63, blk = idx >> 6;
+  if (blk >= (K / 64) * 4 * MS) return;
+  const int ms = blk % MS, h = (blk / MS) & 3, S = blk / (4 * MS);
+  const int r = lane & 15, q = lane >> 4;
+  const int k = 64 * S + 32 * (h >> 1) + 8 * (r >> 2) + 4 * (h & 1) + (r & 3);
+  float w[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const int col = 32 * ms + 8 * q + e;
+    w[e] = col < M ? W[static_cast<size_t>(k) * M + col] : 0.f;
+  }
+  uint4 v;
+  v.x = cvt_pk_f16(w[0], w[1]); v.y = cvt_pk_f16(w[2], w[3]);
+  v.z = cvt_pk_f16(w[4], w[5]); v.w = cvt_pk_f16(w[6], w[7]);
+  Wa[static_cast<size_t>(blk) * 64 + lane] = v;
+}
+
 __device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float acc) {
   return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a), __builtin_bit_cast(bf16x2, b),
                                          acc, false);
@@ -432,7 +454,10 @@ __global__ __launch_bounds__(256, 2) void bwd_reduce_kernel(
 //        g_z u (what g_b and g_alpha are summed from), in a fixed butterfly order
 // Tokens T..Tpad-1 get zero vr so that padded tiles add nothing to g_W.
 // One wave per block, one token per lane.
-template <int N, int MODE>
+// F16ROWS (the single-kernel wide pass 2): the vr ROWS hold fp16 hi, lo parts of
+// vr / s with s = max_m |vr_m| of the token (1 if that is 0), so that any gradient
+// scale fits fp16; s goes to cpk[N*N + 2N + 1].  vrT stays bf16 in either case.
+template <int N, int MODE, bool F16ROWS>
 __global__ __launch_bounds__(64) void bwd_epilogue_fast_kernel(
     const float *__restrict__ u_raw, const float *__restrict__ sumsq, int parts,
     const float *__restrict__ b, const float *__restrict__ alpha, const float *__restrict__ gH_res,
@@ -474,9 +499,22 @@ __global__ __launch_bounds__(64) void bwd_epilogue_fast_kernel(
   }
   token_coeffs_bwd<N, MODE>(gr, gp, gq, a, Hr, Hp, Hq, sums, sk_iters, gz);
   float ga[3] = {0.f, 0.f, 0.f}, dot = 0.f;
-  uint32_t ph[MP32 / 2], pl[MP32 / 2];   // the token's vr row, two bf16 per word
+  uint32_t ph[MP32 / 2], pl[MP32 / 2];   // the token's vr row, two 16-bit parts per word
 #pragma unroll
   for (int i = 0; i < MP32 / 2; ++i) { ph[i] = 0; pl[i] = 0; }
+  float inv_s = 1.f;
+  if constexpr (F16ROWS) {
+    float vmax = 0.f;
+#pragma unroll
+    for (int m = 0; m < M; ++m) {
+      const int g = m < R ? 0 : (m < R + N ? 1 : 2);
+      const float al = g == 0 ? p.alpha_res : (g == 1 ? p.alpha_pre : p.alpha_post);
+      vmax = fmaxf(vmax, fabsf(r * al * (live ? gz[m] : 0.f)));
+    }
+    const float sc = vmax > 0.f ? vmax : 1.f;
+    inv_s = 1.f / sc;
+    if (live) cpk[t * CP + N * N + 2 * N + 1] = sc;
+  }
 #pragma unroll
   for (int m = 0; m < M; ++m) {
     const int g = m < R ? 0 : (m < R + N ? 1 : 2);
@@ -487,10 +525,17 @@ __global__ __launch_bounds__(64) void bwd_epilogue_fast_kernel(
     dot += vr * u[m];
     uint16_t hi, lo;
     split_bf16(vr, hi, lo);
-    ph[m / 2] |= static_cast<uint32_t>(hi) << (16 * (m & 1));
-    pl[m / 2] |= static_cast<uint32_t>(lo) << (16 * (m & 1));
     vrT_hi[(blk * MP16 + m) * 32 + tin] = hi;
     vrT_lo[(blk * MP16 + m) * 32 + tin] = lo;
+    if constexpr (F16ROWS) {
+      const float vs = vr * inv_s;
+      const _Float16 h16 = static_cast<_Float16>(vs);
+      const _Float16 l16 = static_cast<_Float16>(vs - static_cast<float>(h16));
+      hi = __builtin_bit_cast(uint16_t, h16);
+      lo = __builtin_bit_cast(uint16_t, l16);
+    }
+    ph[m / 2] |= static_cast<uint32_t>(hi) << (16 * (m & 1));
+    pl[m / 2] |= static_cast<uint32_t>(lo) << (16 * (m & 1));
   }
 #pragma unroll
   for (int m = M; m < MP16; ++m) {
@@ -832,15 +877,18 @@ __global__ __launch_bounds__(256, 2) void wv_kernel(const u32x4 *__restrict__ Wa
   }
 }
 
-// Pass 2 of the wide case in one kernel, for slices that fit on chip when only the
-// leading bf16 part of W is kept (n = 5: 100 KiB per 64-column step):
-//   g_x[j] = sum_i H_res[i][j] g_xout[i] + H_pre[j] g_h + (W_hi vr)[j] - x[j] coefx
+// Pass 2 of the wide case in one kernel, for slices that fit on chip when W is kept
+// as ONE 16-bit part (n = 5: 100 KiB per 64-column step; the bf16 pair would be 200):
+//   g_x[j] = sum_i H_res[i][j] g_xout[i] + H_pre[j] g_h + (W16 vr)[j] - x[j] coefx
 //   g_y    = sum_i H_post[i] g_xout[i]
-// vr keeps both of its parts.  Rounding W to bf16 in this one product changes
-// (W vr) by about 2^-9 / sqrt(3) of its size, less than the rounding of g_x to bf16
-// that follows.  Nothing is written between the passes (the two-kernel variant
-// stores W vr as fp32 [T, nC] and reads it back).  One block of eight waves per CU,
-// each wave 16 tokens per iteration; lane ownership as in bwd_out_gw_kernel.
+// W16 = fp16(W) (11 significant bits; |W| must stay below 65504, weights are O(1) or
+// less), and vr enters as fp16 hi + lo parts of vr / s with the token's own scale s
+// (bwd_epilogue_fast_kernel, F16ROWS), so gradients of any magnitude fit; the MFMA
+// result is multiplied by s.  Rounding W to fp16 changes (W vr) by about 2^-12 of its
+// size, far below the rounding of g_x to bf16 that follows.  Nothing is written between
+// the passes (the two-kernel variant stores W vr as fp32 [T, nC] and reads it back).
+// One block of eight waves per CU, each wave 16 tokens per iteration; lane ownership
+// as in bwd_out_gw_kernel.
 template <int N, int MS>
 __global__ __launch_bounds__(512, 1) void bwd_out_whi_kernel(
     const uint16_t *__restrict__ x, const uint16_t *__restrict__ g,
@@ -848,9 +896,9 @@ __global__ __launch_bounds__(512, 1) void bwd_out_whi_kernel(
     const uint16_t *__restrict__ vr_hi, const uint16_t *__restrict__ vr_lo, int MP32, int C,
     int64_t T, int tokens_per_block, int CP, uint16_t *__restrict__ g_x,
     uint16_t *__restrict__ g_y) {
-  constexpr int NCP = N * N + 2 * N + 1;
+  constexpr int NCP = N * N + 2 * N + 2;
   constexpr int NCP4 = (NCP + 3) / 4;
-  constexpr int kStreamVec = 4 * MS * 64;       // 16-byte words of W_hi per stream and 64-column step
+  constexpr int kStreamVec = 4 * MS * 64;       // 16-byte words of W16 per stream and 64-column step
   extern __shared__ u32x4 lds[];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int r = lane & 15, q = lane >> 4;
@@ -860,7 +908,7 @@ __global__ __launch_bounds__(512, 1) void bwd_out_whi_kernel(
   for (int e = threadIdx.x; e < N * kStreamVec; e += 512) {
     const int j = e / kStreamVec, rem = e % kStreamVec;
     const int blk = rem >> 6, ln = rem & 63;     // blk = h * MS + ms of step j nS + S
-    lds[e] = Wa[((static_cast<size_t>(j * nS + S) * 4 * MS + blk) * 2 + 0) * 64 + ln];
+    lds[e] = Wa[(static_cast<size_t>(j * nS + S) * 4 * MS + blk) * 64 + ln];
   }
   __syncthreads();
   const u32x4 *wl = lds + lane;
@@ -908,7 +956,7 @@ __global__ __launch_bounds__(512, 1) void bwd_out_whi_kernel(
     for (int e = 0; e < NCP4; ++e) {
       cp[4 * e] = cp4[e].x; cp[4 * e + 1] = cp4[e].y; cp[4 * e + 2] = cp4[e].z; cp[4 * e + 3] = cp4[e].w;
     }
-    const float cx = cp[N * N + 2 * N];
+    const float cx = cp[N * N + 2 * N], vscale = cp[N * N + 2 * N + 1];
     // Stream by stream, both 64-byte halves of a line computed and stored together; the
     // g_xout and g_h tiles stay packed and are unpacked at each use (registers).
     {   // g_y
@@ -945,15 +993,15 @@ __global__ __launch_bounds__(512, 1) void bwd_out_whi_kernel(
 #pragma unroll
           for (int ms = 0; ms < MS; ++ms) {
             const u32x4 wh = wl[((j * 4 + h) * MS + ms) * 64];
-            wv[hh] = mfma16(wh, vbh[ms], wv[hh]);
-            wv[hh] = mfma16(wh, vbl[ms], wv[hh]);
+            wv[hh] = mfma16h(wh, vbh[ms], wv[hh]);
+            wv[hh] = mfma16h(wh, vbl[ms], wv[hh]);
           }
         }
         float xv[8], hv[8], o[8];
         unpack(X[j][u], xv);
         unpack(H[u], hv);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) o[e] = wv[e >> 2][e & 3] - xv[e] * cx + cp[N * N + j] * hv[e];
+        for (int e = 0; e < 8; ++e) o[e] = vscale * wv[e >> 2][e & 3] - xv[e] * cx + cp[N * N + j] * hv[e];
 #pragma unroll
         for (int i = 0; i < N; ++i) {
           float gv[8];
@@ -1375,6 +1423,8 @@ bool fast_bwd_ok(const mhcl_desc &d) { return fast_path_ok(d); }
 // the single-kernel pass 2 exists for the (n, logit tiles) pairs of the full forms with
 // n <= 4; everything else (n >= 5, any permutation subset) takes the wide pass 2
 bool fast_bwd_wide(const mhcl_desc &d) { return d.n > 4 || d.res_mode == MHCL_RES_SUBSET; }
+// n = 5 of the full forms: wide pass 2 in one kernel with W as one fp16 part in LDS
+bool fast_bwd_whi(const mhcl_desc &d) { return d.n == 5 && d.res_mode != MHCL_RES_SUBSET; }
 
 namespace {
 // K steps per wave of bwd_gw_kernel: bounded by its accumulators (2 * NT * 4 registers per step)
@@ -1421,7 +1471,7 @@ FastBwdWs::FastBwdWs(const mhcl_desc &d, void *ws) {
   WsCursor c(ws);
   const size_t T = static_cast<size_t>(d.T), Tpad = (T + 63) / 64 * 64;
   const int n = d.n, M = res_logits(d) + 2 * d.n, K = d.n * d.C;
-  CP = (n * n + 2 * n + 1 + 7) / 8 * 8;   // H_res | H_pre | H_post | coefx, padded
+  CP = (n * n + 2 * n + 2 + 7) / 8 * 8;   // H_res | H_pre | H_post | coefx | scale of the vr row, padded
   MP32 = logit_steps(M) * 32;
   MP16 = logit_tiles(M) * 16;
   parts = fast_bwd_wide(d) ? proj_ksplit(d) : 1;   // the wide path recomputes with proj_mfma_kernel
@@ -1452,6 +1502,11 @@ FastBwdWs::FastBwdWs(const mhcl_desc &d, void *ws) {
 hipError_t launch_pack_w_a(const mhcl_desc &d, int M, const float *W, void *Wa, hipStream_t s) {
   const int K = d.n * d.C, MS = logit_steps(M);
   const int threads = (K / 64) * 4 * MS * 64;
+  if (fast_bwd_whi(d)) {   // the only reader is bwd_out_whi_kernel: one fp16 part
+    hipLaunchKernelGGL(pack_w_a16_kernel, dim3((threads + 255) / 256), dim3(256), 0, s, W, K, M, MS,
+                       static_cast<uint4 *>(Wa));
+    return hipGetLastError();
+  }
   hipLaunchKernelGGL(pack_w_a_kernel, dim3((threads + 255) / 256), dim3(256), 0, s, W, K, M, MS,
                      static_cast<uint4 *>(Wa));
   return hipGetLastError();
@@ -1491,10 +1546,12 @@ hipError_t launch_bwd_epilogue_fast(const mhcl_desc &d, const float *b, const fl
     constexpr int N = decltype(nn)::value, MODE = decltype(mm)::value;
     if (w.MP32 != (Dims<N, MODE>::M + 31) / 32 * 32 || w.MP16 != (Dims<N, MODE>::M + 15) / 16 * 16)
       return hipErrorInvalidValue;
-    hipLaunchKernelGGL((bwd_epilogue_fast_kernel<N, MODE>), dim3(static_cast<unsigned>(Tpad / 64)),
-                       dim3(64), 0, s, w.u_raw, w.sumsq, w.parts, b, alpha, w.gH_res, w.gH_pre,
-                       w.gH_post, d.n * d.C, d.eps, d.sk_iters, d.T, w.CP, w.cpk, w.vr_hi, w.vr_lo,
-                       w.vrT_hi, w.vrT_lo, w.gz);
+    constexpr bool kF16 = N == 5;   // the widths of fast_bwd_whi(): rows for bwd_out_whi_kernel
+    if (kF16 != fast_bwd_whi(d) || (kF16 && w.CP < N * N + 2 * N + 2)) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((bwd_epilogue_fast_kernel<N, MODE, kF16>),
+                       dim3(static_cast<unsigned>(Tpad / 64)), dim3(64), 0, s, w.u_raw, w.sumsq,
+                       w.parts, b, alpha, w.gH_res, w.gH_pre, w.gH_post, d.n * d.C, d.eps,
+                       d.sk_iters, d.T, w.CP, w.cpk, w.vr_hi, w.vr_lo, w.vrT_hi, w.vrT_lo, w.gz);
     return hipGetLastError();
   };
   using L = std::integral_constant<int, MHCL_RES_LITE>;
@@ -1539,8 +1596,9 @@ hipError_t launch_bwd_out_wide(const mhcl_desc &d, int M, const void *x, const v
                                const void *g_h, const FastBwdWs &w, void *g_x, void *g_y,
                                hipStream_t s) {
   const int K = d.n * d.C, MS = logit_steps(M);
-  if (d.n == 5 && (MS == 2 || MS == 5)) {
-    // one kernel, W's leading bf16 part resident in LDS; one round of one block per CU
+  if (fast_bwd_whi(d)) {
+    if (MS != 2 && MS != 5) return hipErrorInvalidValue;
+    // one kernel, W as one fp16 part resident in LDS; one round of one block per CU
     const int64_t xb = d.C / 64;
     int64_t chunks = 256 / xb;
     if (chunks < 1) chunks = 1;

@@ -24,6 +24,21 @@ __device__ __forceinline__ f32x4 mfma16(const u32x4 &a, const u32x4 &b, f32x4 c)
                                                  __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
 }
 
+// the same tile shape and lane layout with fp16 operands
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ f32x4 mfma16h(const u32x4 &a, const u32x4 &b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a),
+                                                __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+}
+// two fp32 -> packed fp16 pair, round to nearest even
+__device__ __forceinline__ uint32_t cvt_pk_f16(float lo, float hi) {
+  f16x2 r;
+  r[0] = static_cast<_Float16>(lo);
+  r[1] = static_cast<_Float16>(hi);
+  return __builtin_bit_cast(uint32_t, r);
+}
+
 // two fp32 -> packed bf16 pair, round to nearest even (v_cvt_pk_bf16_f32)
 __device__ __forceinline__ uint32_t cvt_pk_bf16(float lo, float hi) {
   bf16x2 r;

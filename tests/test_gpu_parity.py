@@ -237,3 +237,26 @@ def test_saturated_gates_stay_finite():
     _check_backward(L, ref, wl, params=False)
     for name in ("g_W", "g_b", "g_alpha"):
         assert rel_err(to_np64(getattr(L, name)), ref[name]) <= TOL_BF16_PARAM, name
+
+
+@pytest.mark.parametrize("n,C", [(4, 256), (5, 128), (3, 64)])
+def test_backward_scales_exactly_with_the_upstream_gradients(n, C):
+    """Upstream gradients 2^-24 and 2^12 times as large (exact in bf16): every backward
+    output scales by the same power of two, bit for bit, with no underflow or overflow
+    on the way (the n = 5 pass 2 carries its per-token vector in fp16 with a scale)."""
+    wl = _small(f"scale_n{n}", n=n, C=C, T=130)
+    inp = si.make_inputs(wl, seed=4, device="cuda")
+    L = GpuLayer(desc_for(wl), inp)
+    L.backward_fused()
+    torch.cuda.synchronize()
+    base = {k: getattr(L, k).float().clone() for k in ("g_x", "g_y", "g_W", "g_b", "g_alpha")}
+    for sc in (2.0 ** -24, 2.0 ** 12):
+        scaled = dict(inp)
+        scaled["g_xout"] = (inp["g_xout"].float() * sc).to(inp["g_xout"].dtype)
+        scaled["g_h"] = (inp["g_h"].float() * sc).to(inp["g_h"].dtype)
+        Ls = GpuLayer(desc_for(wl), scaled)
+        Ls.backward_fused()
+        torch.cuda.synchronize()
+        for k, v in base.items():
+            got = getattr(Ls, k).float() / sc
+            assert torch.equal(got, v), (sc, k, float((got - v).abs().max()))
