@@ -1200,22 +1200,40 @@ __global__ __launch_bounds__(256, 2) void bwd_gw_kernel(
 }
 
 // The same reduction for many logit tiles (n = 5: NT = 9).  Every wave of a block
-// needs the whole vrT block of the 32 tokens at hand (18 KiB), so the block stages
-// it in LDS once (double buffered, requested one iteration ahead) instead of
-// each wave fetching it from L2.
+// needs the whole vrT block of the 32 tokens at hand (18 KiB), so the block (eight
+// waves, one block per CU) stages it in LDS once instead of each wave fetching it
+// from L2.  Both vrT and the waves' own x rows arrive by direct global->LDS loads
+// (lane l of a wave lands at the wave's base + 16 l), requested TWO token blocks
+// ahead: vrT into a ring of three buffers, x into two slots per wave (a slot is free
+// again once its rows are in registers).  Every wave issues the same number of loads
+// per batch (kBatch), so "all but the newest batch have landed" is one
+// s_waitcnt vmcnt(kBatch), and no register waits on memory across iterations.
 template <int NT, int CSW>
-__global__ __launch_bounds__(256, 2) void bwd_gw_lds_kernel(
+struct GwLdsCfg {
+  static constexpr int kThreads = 512;
+  static constexpr int kPartVec = NT * 16 * 4;                   // 16-byte words of one part of a vrT block
+  static constexpr int kBufVec = 2 * kPartVec;
+  static constexpr int WV = (kBufVec + kThreads - 1) / kThreads;  // rounds of the block per buffer
+  static constexpr int kBufPad = WV * kThreads;                  // whole rounds (the surplus lands in padding)
+  static constexpr int kXSlot = 2 * CSW * 64;                    // words of one wave's x rows of a token block
+  static constexpr int kBatch = WV + 2 * CSW;                    // vector-memory instructions per wave and batch
+  static constexpr int kLdsBytes = (3 * kBufPad + 2 * 8 * kXSlot) * 16;
+};
+
+template <int NT, int CSW>
+__global__ __launch_bounds__(512, 1) void bwd_gw_lds_kernel(
     const uint16_t *__restrict__ x, const uint16_t *__restrict__ vrT_hi,
     const uint16_t *__restrict__ vrT_lo, int K, int M, int64_t T, int64_t nblk,
     int blks_per_chunk, float *__restrict__ out) {
-  constexpr int MP16 = NT * 16;
-  constexpr int kPartVec = MP16 * 4;            // 16-byte words of one part (hi or lo) of a block
-  constexpr int kBufVec = 2 * kPartVec;
-  constexpr int WV = (kBufVec + 255) / 256;
-  __shared__ u32x4 lds[2 * kBufVec];
+  using Cfg = GwLdsCfg<NT, CSW>;
+  constexpr int kPartVec = Cfg::kPartVec, kBufVec = Cfg::kBufVec, kBufPad = Cfg::kBufPad;
+  constexpr int kBatch = Cfg::kBatch;
+  static_assert(kBatch <= 15, "the wait below encodes the count in four bits");
+  extern __shared__ u32x4 lds[];
+  u32x4 *xring = lds + 3 * kBufPad;             // [slot][wave][c][gI][lane]
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int r = lane & 15, q = lane >> 4;
-  const int s0 = (blockIdx.x * 4 + wave) * CSW;
+  const int s0 = (blockIdx.x * 8 + wave) * CSW;
   const int nsteps = K / 32;
   u32x4 sel[2];
 #pragma unroll
@@ -1242,80 +1260,91 @@ __global__ __launch_bounds__(256, 2) void bwd_gw_lds_kernel(
 
   const u32x4 *vh = reinterpret_cast<const u32x4 *>(vrT_hi);
   const u32x4 *vl = reinterpret_cast<const u32x4 *>(vrT_lo);
-  u32x4 wst[WV], X[CSW][2];
-  auto load_v = [&](int64_t blk) {
-#pragma unroll
-    for (int i = 0; i < WV; ++i) {
-      int e = i * 256 + threadIdx.x;
-      if (e > kBufVec - 1) e = kBufVec - 1;
-      wst[i] = e < kPartVec ? vh[blk * kPartVec + e] : vl[blk * kPartVec + (e - kPartVec)];
-    }
+  auto to_lds = [](const void *src, u32x4 *dst) {
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
+                                     (__attribute__((address_space(3))) void *)dst, 16, 0, 0);
   };
-  auto store_v = [&](int buf) {
+  // one batch: vrT block `blk` -> ring buffer `vbuf`, this wave's x rows of it -> slot `xs`
+  auto request = [&](int64_t blk, int vbuf, int xs) {
 #pragma unroll
-    for (int i = 0; i < WV; ++i) {
-      int e = i * 256 + threadIdx.x;
-      if (e > kBufVec - 1) e = kBufVec - 1;
-      lds[buf * kBufVec + e] = wst[i];
+    for (int i = 0; i < Cfg::WV; ++i) {
+      int e = i * Cfg::kThreads + threadIdx.x;
+      if (e > kBufVec - 1) e = kBufVec - 1;     // surplus lanes re-read the last word (into padding)
+      // LDS word e of a part = 16-byte piece (e & 3) ^ ((row >> 2) & 3) of row e >> 2: the
+      // 64-byte rows r, r + 4, r + 8, r + 12 would otherwise share their banks
+      const int ep = e < kPartVec ? e : e - kPartVec;
+      const int eg = (ep & ~3) | ((ep & 3) ^ ((ep >> 4) & 3));
+      const u32x4 *src = (e < kPartVec ? vh : vl) + blk * kPartVec + eg;
+      to_lds(src, lds + vbuf * kBufPad + i * Cfg::kThreads + wave * 64);
     }
-  };
-  auto load_x = [&](u32x4 (&d)[CSW][2], int64_t blk) {
 #pragma unroll
-    for (int gI = 0; gI < 2; ++gI) {
-      int64_t t = blk * 32 + gI * 16 + r;
-      if (t > T - 1) t = T - 1;
+    for (int c = 0; c < CSW; ++c) {
+      const int s = s0 + c < nsteps ? s0 + c : nsteps - 1;
 #pragma unroll
-      for (int c = 0; c < CSW; ++c) {
-        const int s = s0 + c < nsteps ? s0 + c : nsteps - 1;
-        d[c][gI] = *reinterpret_cast<const u32x4 *>(x + t * K + s * 32 + q * 8);
+      for (int gI = 0; gI < 2; ++gI) {
+        int64_t t = blk * 32 + gI * 16 + r;
+        if (t > T - 1) t = T - 1;
+        to_lds(x + t * K + s * 32 + q * 8, xring + (xs * 8 + wave) * Cfg::kXSlot + (c * 2 + gI) * 64);
       }
-    }
-  };
-  // nxt: the block whose x rows are requested once this one's are transposed
-  auto process = [&](u32x4 (&xx)[CSW][2], int buf, int64_t nxt) {
-    // lane (logit row r, q) takes tokens 4q..4q+3 and 16+4q..: two 8-byte pieces of its 64-byte row
-    const uint32_t *base = reinterpret_cast<const uint32_t *>(lds + buf * kBufVec);
-    u32x4 bt[CSW][2];
-#pragma unroll
-    for (int c = 0; c < CSW; ++c)
-#pragma unroll
-      for (int h = 0; h < 2; ++h) {
-        const f32x4 z = f32x4{0.f, 0.f, 0.f, 0.f};
-        const f32x4 t0 = mfma16(xx[c][0], sel[h], z);
-        const f32x4 t1 = mfma16(xx[c][1], sel[h], z);
-        bt[c][h].x = cvt_pk_bf16(t0[0], t0[1]); bt[c][h].y = cvt_pk_bf16(t0[2], t0[3]);
-        bt[c][h].z = cvt_pk_bf16(t1[0], t1[1]); bt[c][h].w = cvt_pk_bf16(t1[2], t1[3]);
-      }
-    load_x(xx, nxt);
-#pragma unroll
-    for (int mt = 0; mt < NT; ++mt) {
-      const int row = (mt * 16 + r) * 16 + 2 * q;     // in 4-byte words
-      const u32x2 h0 = *reinterpret_cast<const u32x2 *>(base + row);
-      const u32x2 h1 = *reinterpret_cast<const u32x2 *>(base + row + 8);
-      const u32x2 l0 = *reinterpret_cast<const u32x2 *>(base + kPartVec * 4 + row);
-      const u32x2 l1 = *reinterpret_cast<const u32x2 *>(base + kPartVec * 4 + row + 8);
-      const u32x4 ah = u32x4{h0.x, h0.y, h1.x, h1.y}, al = u32x4{l0.x, l0.y, l1.x, l1.y};
-#pragma unroll
-      for (int c = 0; c < CSW; ++c)
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-          acc[c][h][mt] = mfma16(ah, bt[c][h], acc[c][h][mt]);
-          acc[c][h][mt] = mfma16(al, bt[c][h], acc[c][h][mt]);
-        }
     }
   };
 
   if (b0 < b1) {   // uniform over the block; an empty chunk still writes its zeros
-    load_v(b0);
-    load_x(X, b0);
+    request(b0, 0, 0);
+    request(b0 + 1 < b1 ? b0 + 1 : b0, 1, 1);
     for (int64_t blk = b0; blk < b1; ++blk) {
-      const int buf = static_cast<int>(blk - b0) & 1;
-      store_v(buf);
-      __syncthreads();
-      const int64_t nxt = blk + 1 < b1 ? blk + 1 : blk;
-      load_v(nxt);
-      process(X, buf, nxt);
+      const int i = static_cast<int>(blk - b0);
+      // Everything but the newest batch has landed (vmcnt(kBatch)), this wave's LDS
+      // reads of the previous block are done (lgkmcnt(0)), then the barrier.  Written
+      // out because __syncthreads() carries a release fence that waits for ALL
+      // outstanding vector-memory operations, the prefetched batch included.
+      __builtin_amdgcn_sched_barrier(0);
+      asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" : : "n"(kBatch) : "memory");
+      __builtin_amdgcn_sched_barrier(0);
+      const u32x4 *xs = xring + ((i & 1) * 8 + wave) * Cfg::kXSlot + lane;
+      u32x4 bt[CSW][2];
+#pragma unroll
+      for (int c = 0; c < CSW; ++c) {
+        const u32x4 x0 = xs[(c * 2 + 0) * 64], x1 = xs[(c * 2 + 1) * 64];
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+          const f32x4 z = f32x4{0.f, 0.f, 0.f, 0.f};
+          const f32x4 t0 = mfma16(x0, sel[h], z);
+          const f32x4 t1 = mfma16(x1, sel[h], z);
+          bt[c][h].x = cvt_pk_bf16(t0[0], t0[1]); bt[c][h].y = cvt_pk_bf16(t0[2], t0[3]);
+          bt[c][h].z = cvt_pk_bf16(t1[0], t1[1]); bt[c][h].w = cvt_pk_bf16(t1[2], t1[3]);
+        }
+      }
+      // the x slot has been read into registers (the products above used it): refill it,
+      // and the vrT buffer that was read two blocks ago
+      __builtin_amdgcn_sched_barrier(0);
+      asm volatile("s_waitcnt lgkmcnt(0)" : : : "memory");
+      request(blk + 2 < b1 ? blk + 2 : b1 - 1, (i + 2) % 3, i & 1);   // past the end: the last block again
+      __builtin_amdgcn_sched_barrier(0);
+      // lane (logit row r, q) takes tokens 4q..4q+3 and 16+4q..: two 8-byte pieces of its 64-byte row
+      const uint32_t *base = reinterpret_cast<const uint32_t *>(lds + (i % 3) * kBufPad);
+#pragma unroll
+      for (int mt = 0; mt < NT; ++mt) {
+        // pieces (q >> 1) and 2 + (q >> 1) of the row, at their swizzled places; in 4-byte words
+        const int sw = (r >> 2) & 3;
+        const int row = (mt * 16 + r) * 16 + (q & 1) * 2;
+        const int p0 = row + (((q >> 1) ^ sw) << 2), p1 = row + (((2 + (q >> 1)) ^ sw) << 2);
+        const u32x2 h0 = *reinterpret_cast<const u32x2 *>(base + p0);
+        const u32x2 h1 = *reinterpret_cast<const u32x2 *>(base + p1);
+        const u32x2 l0 = *reinterpret_cast<const u32x2 *>(base + kPartVec * 4 + p0);
+        const u32x2 l1 = *reinterpret_cast<const u32x2 *>(base + kPartVec * 4 + p1);
+        const u32x4 ah = u32x4{h0.x, h0.y, h1.x, h1.y}, al = u32x4{l0.x, l0.y, l1.x, l1.y};
+#pragma unroll
+        for (int c = 0; c < CSW; ++c)
+#pragma unroll
+          for (int h = 0; h < 2; ++h) {
+            acc[c][h][mt] = mfma16(ah, bt[c][h], acc[c][h][mt]);
+            acc[c][h][mt] = mfma16(al, bt[c][h], acc[c][h][mt]);
+          }
+      }
     }
+    // nothing may still be writing LDS when the block ends
+    asm volatile("s_waitcnt vmcnt(0)" : : : "memory");
   }
 
   float *dst = out + static_cast<size_t>(blockIdx.y) * K * M;
@@ -1432,7 +1461,8 @@ int gw_csw(const mhcl_desc &d) {
   return logit_tiles(res_logits(d) + 2 * d.n) <= 3 ? 4 : 2;
 }
 int gw_xblocks(const mhcl_desc &d) {
-  const int per_block = 4 * gw_csw(d);
+  const bool lds_kernel = logit_tiles(res_logits(d) + 2 * d.n) > 3;   // eight waves per block there
+  const int per_block = (lds_kernel ? 8 : 4) * gw_csw(d);
   return (d.n * d.C / 32 + per_block - 1) / per_block;
 }
 }  // namespace
@@ -1458,9 +1488,10 @@ int out_gw_tokens_per_block(const mhcl_desc &d) {
 
 int gw_chunks_fast(const mhcl_desc &d) {
   const int64_t nblk = (d.T + 31) / 32;
-  // two blocks fit a compute unit: the largest chunk count that keeps the grid at
-  // one round of 512 blocks
-  int64_t c = 512 / gw_xblocks(d);
+  // the largest chunk count that keeps the grid at one round of resident blocks (one
+  // eight-wave block per compute unit in the LDS kernel, two four-wave blocks otherwise)
+  const bool lds_kernel = logit_tiles(res_logits(d) + 2 * d.n) > 3;
+  int64_t c = (lds_kernel ? 256 : 512) / gw_xblocks(d);
   if (c > 64) c = 64;
   if (c > nblk) c = nblk;
   if (c < 1) c = 1;
@@ -1581,7 +1612,14 @@ hipError_t launch_bwd_gw(const mhcl_desc &d, int M, const void *x, const FastBwd
                          static_cast<const uint16_t *>(x), w.vrT_hi, w.vrT_lo, K, M, w.MP16, d.T,
                          nblk, bpc, dst);
     } else {
-      hipLaunchKernelGGL((bwd_gw_lds_kernel<NT, 2>), dim3(gw_xblocks(d), chunks), dim3(256), 0, s,
+      auto kern = bwd_gw_lds_kernel<NT, 2>;
+      constexpr int lds = GwLdsCfg<NT, 2>::kLdsBytes;
+      if (lds > 64 * 1024) {
+        hipError_t e1 = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        if (e1 != hipSuccess) return e1;
+      }
+      hipLaunchKernelGGL(kern, dim3(gw_xblocks(d), chunks), dim3(512), lds, s,
                          static_cast<const uint16_t *>(x), w.vrT_hi, w.vrT_lo, K, M, d.T, nblk, bpc,
                          dst);
     }
