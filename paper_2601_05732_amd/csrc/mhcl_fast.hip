@@ -1208,6 +1208,8 @@ __global__ __launch_bounds__(256, 2) void bwd_gw_kernel(
 // again once its rows are in registers).  Every wave issues the same number of loads
 // per batch (kBatch), so "all but the newest batch have landed" is one
 // s_waitcnt vmcnt(kBatch), and no register waits on memory across iterations.
+// (The count relies on one vector-memory instruction per to_lds() call and no other
+// vector-memory access inside the loop; the compiled loop holds exactly kBatch.)
 template <int NT, int CSW>
 struct GwLdsCfg {
   static constexpr int kThreads = 512;
