@@ -399,7 +399,7 @@ int mhcl_bwd_fused(const mhcl_desc *desc, const void *x, const void *y, const fl
       StageBracket br(MHCL_STAGE_BWD_REDUCE, s);
       if (wide) {
         MHCL_HIP(launch_proj_mfma(*desc, M, x, f.Wp, f.u_raw, f.sumsq, s));
-        MHCL_HIP(launch_bwd_dots(*desc, x, y, g_xout, g_h, f.gH_res, f.gH_post, f.gH_pre, s));
+        MHCL_HIP(launch_bwd_dots_fast(*desc, x, y, g_xout, g_h, f, s));
       } else {
         MHCL_HIP(launch_bwd_reduce(*desc, M, x, y, g_xout, g_h, f, s));
       }

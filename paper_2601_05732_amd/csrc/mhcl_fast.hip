@@ -445,6 +445,72 @@ __global__ __launch_bounds__(256, 2) void bwd_reduce_kernel(
 }
 
 // ---------------------------------------------------------------------------
+// The dot products of pass 1 alone (wide case, where the projection runs in
+// proj_mfma_kernel): g_H_res, g_H_post, g_H_pre from one read of x, g_xout, y, g_h.
+// Same tiles, lane ownership and v_dot2_f32_bf16 arithmetic as bwd_reduce_kernel; no
+// W, no LDS, no barrier.  Block = 4 waves x 16 tokens.
+template <int N>
+__global__ __launch_bounds__(256) void bwd_dots_fast_kernel(
+    const uint16_t *__restrict__ x, const uint16_t *__restrict__ y,
+    const uint16_t *__restrict__ g, const uint16_t *__restrict__ gh, int C, int64_t T,
+    float *__restrict__ gH_res, float *__restrict__ gH_post, float *__restrict__ gH_pre) {
+  constexpr int D = N * N + 2 * N;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int r = lane & 15, q = lane >> 4;
+  const int64_t tw = static_cast<int64_t>(blockIdx.x) * 64 + wave * 16;
+  int64_t tl = tw + r;
+  if (tl > T - 1) tl = T - 1;
+  const uint16_t *xr = x + tl * N * C + q * 8;
+  const uint16_t *gr = g + tl * N * C + q * 8;
+  const uint16_t *yr = y + tl * C + q * 8;
+  const uint16_t *hr = gh + tl * C + q * 8;
+  const int ncs = C / 64;
+  float dots[D];
+#pragma unroll
+  for (int e = 0; e < D; ++e) dots[e] = 0.f;
+  for (int cs = 0; cs < ncs; ++cs) {
+    u32x4 X[N][2], G[N][2], Y[2], H[2];
+#pragma unroll
+    for (int j = 0; j < N; ++j)
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        X[j][u] = *reinterpret_cast<const u32x4 *>(xr + j * C + cs * 64 + u * 32);
+        G[j][u] = *reinterpret_cast<const u32x4 *>(gr + j * C + cs * 64 + u * 32);
+      }
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      Y[u] = *reinterpret_cast<const u32x4 *>(yr + cs * 64 + u * 32);
+      H[u] = *reinterpret_cast<const u32x4 *>(hr + cs * 64 + u * 32);
+    }
+#pragma unroll
+    for (int j = 0; j < N; ++j)
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+#pragma unroll
+        for (int i = 0; i < N; ++i) dots[i * N + j] = dot8_bf16(G[i][u], X[j][u], dots[i * N + j]);
+        dots[N * N + j] = dot8_bf16(G[j][u], Y[u], dots[N * N + j]);
+        dots[N * N + N + j] = dot8_bf16(H[u], X[j][u], dots[N * N + N + j]);
+      }
+  }
+  // the four lanes (q = 0..3) of a token hold disjoint column subsets
+#pragma unroll
+  for (int e = 0; e < D; ++e) {
+    dots[e] += __shfl_xor(dots[e], 16, 64);
+    dots[e] += __shfl_xor(dots[e], 32, 64);
+  }
+  const int64_t t = tw + r;
+  if (q == 0 && t < T) {
+#pragma unroll
+    for (int e = 0; e < N * N; ++e) gH_res[t * N * N + e] = dots[e];
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+      gH_post[t * N + i] = dots[N * N + i];
+      gH_pre[t * N + i] = dots[N * N + N + i];
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
 // Per-token stage between the two backward passes: coefficients (recomputed),
 // g_z, and the operands pass 2 needs, in the layouts its MFMAs read:
 //   cpk  [T][CP] f32 : H_res (N*N) | H_pre (N) | H_post (N) | coefx
@@ -1568,6 +1634,30 @@ hipError_t launch_bwd_reduce(const mhcl_desc &d, int M, const void *x, const voi
     case 21: return go(I2{}, I1{});   // lite M=6, SK M=8
     case 31: return go(I3{}, I1{});   // lite M=12, SK M=15
     case 42: return go(I4{}, I2{});   // lite M=32, SK M=24
+  }
+  return hipErrorInvalidValue;
+}
+
+// pass 1 of the wide case without the projection: the dot products alone
+hipError_t launch_bwd_dots_fast(const mhcl_desc &d, const void *x, const void *y, const void *g_xout,
+                                const void *g_h, const FastBwdWs &w, hipStream_t s) {
+  auto go = [&](auto nn) {
+    constexpr int N = decltype(nn)::value;
+    hipLaunchKernelGGL(bwd_dots_fast_kernel<N>, dim3(static_cast<unsigned>((d.T + 63) / 64)),
+                       dim3(256), 0, s, static_cast<const uint16_t *>(x),
+                       static_cast<const uint16_t *>(y), static_cast<const uint16_t *>(g_xout),
+                       static_cast<const uint16_t *>(g_h), d.C, d.T, w.gH_res, w.gH_post, w.gH_pre);
+    return hipGetLastError();
+  };
+  switch (d.n) {
+    case 1: return go(std::integral_constant<int, 1>{});
+    case 2: return go(std::integral_constant<int, 2>{});
+    case 3: return go(std::integral_constant<int, 3>{});
+    case 4: return go(std::integral_constant<int, 4>{});
+    case 5: return go(std::integral_constant<int, 5>{});
+    case 6: return go(std::integral_constant<int, 6>{});
+    case 7: return go(std::integral_constant<int, 7>{});
+    case 8: return go(std::integral_constant<int, 8>{});
   }
   return hipErrorInvalidValue;
 }

@@ -128,6 +128,8 @@ hipError_t launch_pack_w_a(const mhcl_desc &d, int M, const float *W, void *Wa, 
 hipError_t launch_bwd_reduce(const mhcl_desc &d, int M, const void *x, const void *y,
                              const void *g_xout, const void *g_h, const FastBwdWs &w,
                              hipStream_t s);
+hipError_t launch_bwd_dots_fast(const mhcl_desc &d, const void *x, const void *y, const void *g_xout,
+                                const void *g_h, const FastBwdWs &w, hipStream_t s);
 hipError_t launch_bwd_epilogue_fast(const mhcl_desc &d, const float *b, const float *alpha,
                                     const FastBwdWs &w, hipStream_t s);
 // the same stage for the permutation-subset form (run-time table)
