@@ -156,7 +156,7 @@ def main():
                          "of known traffic, to scale hardware byte counters with)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (tokens are independent, so the path "
+        print("bench.py: this benchmark runs on one GPU only (tokens are independent, so the path "
               "shards over tokens; no multi-GPU figure is produced). Use --gpus 1.",
               file=sys.stderr)
         sys.exit(2)

@@ -70,7 +70,7 @@ extern "C" {
 typedef enum {
   MHCL_OK = 0,
   MHCL_ERR_INVALID_ARG = 1, /* null pointer, misaligned pointer, bad enum, n/C/T out of range */
-  MHCL_ERR_UNSUPPORTED = 2, /* a valid description this build has no kernel for */
+  MHCL_ERR_UNSUPPORTED = 2, /* a valid description the library has no kernel for */
   MHCL_ERR_WORKSPACE = 3,   /* ws is null or smaller than mhcl_workspace_bytes() */
   MHCL_ERR_HIP = 4          /* a kernel launch was rejected by the runtime */
 } mhcl_status;
