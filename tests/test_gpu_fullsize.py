@@ -93,8 +93,10 @@ def test_full_size_parameter_gradients(name):
         Ls.backward_fused()
         torch.cuda.synchronize()
         parts.append({k: getattr(Ls, k).double().clone() for k in ("g_W", "g_b", "g_alpha")})
-        # the split run's per-token outputs equal the full run's, bit for bit
-        assert torch.equal(Ls.g_x, L.g_x[sl]) and torch.equal(Ls.g_y, L.g_y[sl])
+        # the split run's per-token outputs equal the full run's up to one bf16 rounding (a
+        # token's sums over C start at a column that depends on its block: another association)
+        for nm in ("g_x", "g_y"):
+            assert rel_err(to_np64(getattr(Ls, nm)), to_np64(getattr(L, nm)[sl])) <= 2.0 ** -7, nm
         del Ls
     for k in full:
         tot = parts[0][k] + parts[1][k]
@@ -145,5 +147,4 @@ def test_tensors_beyond_2_31_elements():
     for nm in ("H_res", "H_pre", "H_post", "h", "x_out", "g_x", "g_y"):
         tol = 3e-5 if nm.startswith("H") else 2.0 ** -7
         assert rel_err(to_np64(getattr(Ls, nm)), to_np64(getattr(L, nm)[t0:])) <= tol, nm
-    assert torch.equal(Ls.g_x, L.g_x[t0:]) and torch.equal(Ls.g_y, L.g_y[t0:])   # backward: same order
     assert torch.isfinite(L.g_W).all() and torch.isfinite(L.g_b).all()
