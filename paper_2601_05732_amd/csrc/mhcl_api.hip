@@ -393,8 +393,7 @@ int mhcl_bwd_fused(const mhcl_desc *desc, const void *x, const void *y, const fl
   if (fast_bwd_ok(*desc)) {
     FastBwdWs f(*desc, ws);
     const bool wide = fast_bwd_wide(*desc);
-    MHCL_HIP(launch_pack_w_b(*desc, M, W, f.Wp, s));
-    MHCL_HIP(launch_pack_w_a(*desc, M, W, f.Wa, s));
+    MHCL_HIP(launch_pack_w_ab(*desc, M, W, f.Wp, f.Wa, s));
     {
       StageBracket br(MHCL_STAGE_BWD_REDUCE, s);
       if (wide) {
@@ -419,7 +418,9 @@ int mhcl_bwd_fused(const mhcl_desc *desc, const void *x, const void *y, const fl
       StageBracket br(MHCL_STAGE_BWD_OUT, s);
       MHCL_HIP(launch_bwd_out_gw(*desc, M, x, g_xout, g_h, f, g_x, g_y, g_W, s));
     }
-    MHCL_HIP(launch_param_sums_rows((desc->T + 63) / 64, M, f.gz, g_b, g_alpha, f.psum, s));
+    MHCL_HIP(launch_bwd_finish(f.partials, static_cast<size_t>(desc->n) * desc->C * M,
+                               fast_gw_chunks(*desc), g_W, f.gz, (desc->T + 63) / 64, M, g_b, g_alpha,
+                               s));
     return MHCL_OK;
   }
   BwdWs w(*desc, ws, true);

@@ -18,9 +18,8 @@ __device__ __forceinline__ void split_bf16(float w, uint16_t &hi, uint16_t &lo) 
 }
 
 // W [K, M] fp32 -> B layout (see mhcl_mfma.h).  One thread per (block pair, lane).
-__global__ __launch_bounds__(256) void pack_w_b_kernel(const float *__restrict__ W, int K, int M,
-                                                       int NT, uint4 *__restrict__ Wp) {
-  const int idx = blockIdx.x * 256 + threadIdx.x;
+__device__ __forceinline__ void pack_w_b_thread(int idx, const float *__restrict__ W, int K, int M,
+                                                int NT, uint4 *__restrict__ Wp) {
   const int lane = idx & 63, blk = idx >> 6;   // blk = s*NT + j
   if (blk >= (K / 32) * NT) return;
   const int s = blk / NT, j = blk % NT, r = lane & 15, q = lane >> 4;
@@ -39,6 +38,11 @@ __global__ __launch_bounds__(256) void pack_w_b_kernel(const float *__restrict__
   vl.z = lo[4] | (uint32_t(lo[5]) << 16); vl.w = lo[6] | (uint32_t(lo[7]) << 16);
   Wp[(static_cast<size_t>(blk) * 2 + 0) * 64 + lane] = vh;
   Wp[(static_cast<size_t>(blk) * 2 + 1) * 64 + lane] = vl;
+}
+
+__global__ __launch_bounds__(256) void pack_w_b_kernel(const float *__restrict__ W, int K, int M,
+                                                       int NT, uint4 *__restrict__ Wp) {
+  pack_w_b_thread(blockIdx.x * 256 + threadIdx.x, W, K, M, NT, Wp);
 }
 
 // ---------------------------------------------------------------------------
@@ -225,9 +229,8 @@ __global__ __launch_bounds__(256, 2) void proj_mfma_kernel(const uint16_t *__res
 
 
 // W [K, M] fp32 -> A layout (see mhcl_mfma.h).  One thread per (block pair, lane).
-__global__ __launch_bounds__(256) void pack_w_a_kernel(const float *__restrict__ W, int K, int M,
-                                                       int MS, uint4 *__restrict__ Wa) {
-  const int idx = blockIdx.x * 256 + threadIdx.x;
+__device__ __forceinline__ void pack_w_a_thread(int idx, const float *__restrict__ W, int K, int M,
+                                                int MS, uint4 *__restrict__ Wa) {
   const int lane = idx & 63, blk = idx >> 6;   // blk = (S*4 + h)*MS + ms
   if (blk >= (K / 64) * 4 * MS) return;
   const int ms = blk % MS, h = (blk / MS) & 3, S = blk / (4 * MS);
@@ -251,9 +254,8 @@ __global__ __launch_bounds__(256) void pack_w_a_kernel(const float *__restrict__
 
 // W [K, M] fp32 -> A layout with ONE fp16 part per block (11 significant bits): for the
 // single-kernel wide pass 2, whose LDS holds one part only.  Block index (S*4 + h)*MS + ms.
-__global__ __launch_bounds__(256) void pack_w_a16_kernel(const float *__restrict__ W, int K, int M,
-                                                         int MS, uint4 *__restrict__ Wa) {
-  const int idx = blockIdx.x * 256 + threadIdx.x;
+__device__ __forceinline__ void pack_w_a16_thread(int idx, const float *__restrict__ W, int K, int M,
+                                                  int MS, uint4 *__restrict__ Wa) {
   const int lane = idx & 63, blk = idx >> 6;
   if (blk >= (K / 64) * 4 * MS) return;
   const int ms = blk % MS, h = (blk / MS) & 3, S = blk / (4 * MS);
@@ -269,6 +271,22 @@ __global__ __launch_bounds__(256) void pack_w_a16_kernel(const float *__restrict
   v.x = cvt_pk_f16(w[0], w[1]); v.y = cvt_pk_f16(w[2], w[3]);
   v.z = cvt_pk_f16(w[4], w[5]); v.w = cvt_pk_f16(w[6], w[7]);
   Wa[static_cast<size_t>(blk) * 64 + lane] = v;
+}
+
+// Both layouts the backward needs in one launch: blocks [0, nb_b) write the B layout
+// (pass 1's projection), the rest the A layout (pass 2), with one fp16 part if `a16`.
+__global__ __launch_bounds__(256) void pack_w_ab_kernel(const float *__restrict__ W, int K, int M,
+                                                        int NT, int MS, int nb_b, int a16,
+                                                        uint4 *__restrict__ Wp,
+                                                        uint4 *__restrict__ Wa) {
+  const int b = blockIdx.x;
+  if (b < nb_b) {
+    pack_w_b_thread(b * 256 + threadIdx.x, W, K, M, NT, Wp);
+  } else if (a16) {
+    pack_w_a16_thread((b - nb_b) * 256 + threadIdx.x, W, K, M, MS, Wa);
+  } else {
+    pack_w_a_thread((b - nb_b) * 256 + threadIdx.x, W, K, M, MS, Wa);
+  }
 }
 
 __device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float acc) {
@@ -1610,16 +1628,14 @@ FastBwdWs::FastBwdWs(const mhcl_desc &d, void *ws) {
   bytes = c.off;
 }
 
-hipError_t launch_pack_w_a(const mhcl_desc &d, int M, const float *W, void *Wa, hipStream_t s) {
-  const int K = d.n * d.C, MS = logit_steps(M);
-  const int threads = (K / 64) * 4 * MS * 64;
-  if (fast_bwd_whi(d)) {   // the only reader is bwd_out_whi_kernel: one fp16 part
-    hipLaunchKernelGGL(pack_w_a16_kernel, dim3((threads + 255) / 256), dim3(256), 0, s, W, K, M, MS,
-                       static_cast<uint4 *>(Wa));
-    return hipGetLastError();
-  }
-  hipLaunchKernelGGL(pack_w_a_kernel, dim3((threads + 255) / 256), dim3(256), 0, s, W, K, M, MS,
-                     static_cast<uint4 *>(Wa));
+hipError_t launch_pack_w_ab(const mhcl_desc &d, int M, const float *W, void *Wp, void *Wa,
+                            hipStream_t s) {
+  const int K = d.n * d.C, NT = logit_tiles(M), MS = logit_steps(M);
+  const int nb_b = ((K / 32) * NT * 64 + 255) / 256;
+  const int nb_a = ((K / 64) * 4 * MS * 64 + 255) / 256;
+  // one fp16 part where the only reader is bwd_out_whi_kernel
+  hipLaunchKernelGGL(pack_w_ab_kernel, dim3(nb_b + nb_a), dim3(256), 0, s, W, K, M, NT, MS, nb_b,
+                     fast_bwd_whi(d) ? 1 : 0, static_cast<uint4 *>(Wp), static_cast<uint4 *>(Wa));
   return hipGetLastError();
 }
 
@@ -1737,8 +1753,7 @@ hipError_t launch_bwd_gw(const mhcl_desc &d, int M, const void *x, const FastBwd
     }
     return hipGetLastError();
   });
-  if (e != hipSuccess || chunks == 1) return e;
-  return launch_sum_partials(w.partials, static_cast<size_t>(K) * M, chunks, g_W, s);
+  return e;   // the chunks' partial sums are added by launch_bwd_finish
 }
 
 // wide pass 2: D = W vr, then g_x and g_y
@@ -1822,7 +1837,6 @@ hipError_t launch_bwd_out_wide(const mhcl_desc &d, int M, const void *x, const v
 hipError_t launch_bwd_out_gw(const mhcl_desc &d, int M, const void *x, const void *g_xout,
                              const void *g_h, const FastBwdWs &w, void *g_x, void *g_y, float *g_W,
                              hipStream_t s) {
-  const int K = d.n * d.C;
   const int tpb = out_gw_tokens_per_block(d);
   const int chunks = static_cast<int>((d.T + tpb - 1) / tpb);
   float *dst = chunks == 1 ? g_W : w.partials;
@@ -1859,8 +1873,14 @@ hipError_t launch_bwd_out_gw(const mhcl_desc &d, int M, const void *x, const voi
     case 31: e = go(I3{}, I1{}); break;
     case 42: e = go(I4{}, I2{}); break;
   }
-  if (e != hipSuccess || chunks == 1) return e;
-  return launch_sum_partials(w.partials, static_cast<size_t>(K) * M, chunks, g_W, s);
+  return e;   // the chunks' partial sums are added by launch_bwd_finish
+}
+
+// number of token chunks whose g_W partial sums the backward leaves in the workspace
+int fast_gw_chunks(const mhcl_desc &d) {
+  if (fast_bwd_wide(d)) return gw_chunks_fast(d);
+  const int tpb = out_gw_tokens_per_block(d);
+  return static_cast<int>((d.T + tpb - 1) / tpb);
 }
 
 }  // namespace mhcl

@@ -551,6 +551,49 @@ __global__ __launch_bounds__(kBlock) void colsum_stage2_kernel(const float *__re
   }
 }
 
+// The end of the fused backward in one launch.  Blocks [0, nbW): g_W = sum over the token
+// chunks' partial sums (as sum_partials_kernel).  Block nbW + c: column c of the
+// [rows, ld] matrix of per-64-token g_z sums, added in a fixed order (thread i takes rows
+// i, i + 256, ... in turn, then a pairwise tree over the threads); columns below nA go to
+// dstA (g_b), the others to dstB (g_alpha).
+__global__ __launch_bounds__(kBlock) void bwd_finish_kernel(const float *__restrict__ part,
+                                                            size_t size, int chunks, int nbW,
+                                                            float *__restrict__ out,
+                                                            const float *__restrict__ src,
+                                                            int64_t rows, int ld, int nA,
+                                                            float *__restrict__ dstA,
+                                                            float *__restrict__ dstB) {
+  __shared__ float red[kBlock];
+  if (static_cast<int>(blockIdx.x) < nbW) {
+    const int el = threadIdx.x & 63, grp = threadIdx.x >> 6;
+    const size_t i = static_cast<size_t>(blockIdx.x) * 64 + el;
+    float s = 0.f;
+    if (i < size) {
+#pragma unroll 4
+      for (int c = grp; c < chunks; c += 4) s += part[c * size + i];
+    }
+    red[grp * 64 + el] = s;
+    __syncthreads();
+    if (grp == 0 && i < size) out[i] = ((red[el] + red[64 + el]) + red[128 + el]) + red[192 + el];
+    return;
+  }
+  const int c = static_cast<int>(blockIdx.x) - nbW;
+  float s = 0.f;
+#pragma unroll 4
+  for (int64_t r = threadIdx.x; r < rows; r += kBlock) s += src[r * ld + c];
+  red[threadIdx.x] = s;
+  __syncthreads();
+#pragma unroll
+  for (int w = kBlock / 2; w > 0; w >>= 1) {
+    if (static_cast<int>(threadIdx.x) < w) red[threadIdx.x] += red[threadIdx.x + w];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    if (c < nA) dstA[c] = red[0];
+    else dstB[c - nA] = red[0];
+  }
+}
+
 __global__ __launch_bounds__(kBlock) void fill_zero_kernel(float *__restrict__ p, size_t count) {
   const size_t i = static_cast<size_t>(blockIdx.x) * kBlock + threadIdx.x;
   if (i < count) p[i] = 0.f;
@@ -740,10 +783,12 @@ hipError_t launch_gw_generic(const mhcl_desc &d, int M, const void *x, const flo
   });
 }
 
-hipError_t launch_sum_partials(const float *partials, size_t size, int chunks, float *out,
-                               hipStream_t s) {
-  hipLaunchKernelGGL(sum_partials_kernel, dim3(blocks_for(size, 64)), dim3(kBlock), 0, s,
-                     partials, size, chunks, out);
+hipError_t launch_bwd_finish(const float *partials, size_t size, int chunks, float *g_W,
+                             const float *gz_rows, int64_t rows, int M, float *g_b, float *g_alpha,
+                             hipStream_t s) {
+  const int nbW = chunks > 1 ? static_cast<int>(blocks_for(size, 64)) : 0;
+  hipLaunchKernelGGL(bwd_finish_kernel, dim3(nbW + M + 3), dim3(kBlock), 0, s, partials, size, chunks,
+                     nbW, g_W, gz_rows, rows, M + 3, M, g_b, g_alpha);
   return hipGetLastError();
 }
 

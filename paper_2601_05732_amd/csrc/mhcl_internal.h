@@ -124,7 +124,8 @@ struct FastBwdWs {
   size_t bytes;
   FastBwdWs(const mhcl_desc &d, void *ws);
 };
-hipError_t launch_pack_w_a(const mhcl_desc &d, int M, const float *W, void *Wa, hipStream_t s);
+hipError_t launch_pack_w_ab(const mhcl_desc &d, int M, const float *W, void *Wp, void *Wa,
+                            hipStream_t s);
 hipError_t launch_bwd_reduce(const mhcl_desc &d, int M, const void *x, const void *y,
                              const void *g_xout, const void *g_h, const FastBwdWs &w,
                              hipStream_t s);
@@ -143,7 +144,11 @@ hipError_t launch_bwd_out_gw(const mhcl_desc &d, int M, const void *x, const voi
                              hipStream_t s);
 hipError_t launch_bwd_gw(const mhcl_desc &d, int M, const void *x, const FastBwdWs &w, float *g_W,
                          hipStream_t s);
-hipError_t launch_sum_partials(const float *partials, size_t size, int chunks, float *out,
-                               hipStream_t s);
+// g_W from the chunks' partial sums (none if chunks == 1) and g_b, g_alpha from the
+// [rows, M+3] per-64-token sums of g_z, in one launch
+hipError_t launch_bwd_finish(const float *partials, size_t size, int chunks, float *g_W,
+                             const float *gz_rows, int64_t rows, int M, float *g_b, float *g_alpha,
+                             hipStream_t s);
+int fast_gw_chunks(const mhcl_desc &d);
 
 }  // namespace mhcl
