@@ -49,7 +49,7 @@ __global__ __launch_bounds__(256) void pack_w_b_kernel(const float *__restrict__
 // Forward projection: u_raw[t][m] = sum_k x_hat[t][k] W[k][m], sumsq[t] = sum_k
 // x_hat[t][k]^2 (RMSNorm's statistic), both from ONE read of x.
 //
-// Block = 4 waves, each wave owns 32 tokens (two 16-token A tiles) and walks
+// Block = 8 waves, each wave owns one or two 16-token A tiles and walks
 // the whole K = nC range; the block's waves share each chunk of packed W
 // through LDS (double buffered).  A tiles come straight from HBM in MFMA lane
 // order: lane (r, q) reads 16 bytes of token r at column 32 s + 8 q, several
@@ -58,21 +58,19 @@ __global__ __launch_bounds__(256) void pack_w_b_kernel(const float *__restrict__
 // the A tile as both operands.
 template <int NT>
 struct ProjCfg {
-#ifndef MHCL_PROJ_KC
-#define MHCL_PROJ_KC 4
-#endif
-#ifndef MHCL_PROJ_TG
-#define MHCL_PROJ_TG 2
-#endif
-  static constexpr int KC = NT == 2 ? MHCL_PROJ_KC : (NT >= 4 ? 2 : 4);   // K steps per chunk
-  static constexpr int TG = NT == 2 ? MHCL_PROJ_TG : 2;        // 16-token A tiles per wave
-  static constexpr int kTokens = 64 * TG;                      // tokens per block
+  static constexpr int KC = NT >= 4 ? 2 : 4;        // K steps per chunk
+  static constexpr int TG = NT <= 3 ? 1 : 2;        // 16-token A tiles per wave
+  // eight waves share each W chunk: one block per CU, half the W traffic from L2 of two
+  // four-wave blocks (0.23 -> 0.21 ms at n = 4, C = 4096)
+  static constexpr int WAVES = 8;
+  static constexpr int kThreads = 64 * WAVES;
+  static constexpr int kTokens = 16 * WAVES * TG;              // tokens per block
   static constexpr int kChunkVec = KC * NT * 2 * 64;           // u32x4 per chunk
   static constexpr int kLdsBytes = 2 * kChunkVec * 16;
 };
 
 template <int NT>
-__global__ __launch_bounds__(256, 2) void proj_mfma_kernel(const uint16_t *__restrict__ x,
+__global__ __launch_bounds__(ProjCfg<NT>::kThreads, 1) void proj_mfma_kernel(const uint16_t *__restrict__ x,
                                                            const u32x4 *__restrict__ Wp, int K,
                                                            int M, int64_t T,
                                                            float *__restrict__ u_raw,
@@ -110,7 +108,8 @@ __global__ __launch_bounds__(256, 2) void proj_mfma_kernel(const uint16_t *__res
     for (int j = 0; j < NT; ++j) acc[g][j] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
 
-  constexpr int WV = Cfg::kChunkVec / 256;   // u32x4 of W each thread stages per chunk
+  constexpr int WV = (Cfg::kChunkVec + Cfg::kThreads - 1) / Cfg::kThreads;   // u32x4 of W each thread stages per chunk
+  constexpr bool kWholeW = Cfg::kChunkVec % Cfg::kThreads == 0;
   u32x4 a[2][TG][KC], wst[WV];
   const int wlim = nsteps * NT * 2 * 64 - 1;   // last valid u32x4 of packed W
 
@@ -134,13 +133,19 @@ __global__ __launch_bounds__(256, 2) void proj_mfma_kernel(const uint16_t *__res
     const int base = c * Cfg::kChunkVec;
 #pragma unroll
     for (int i = 0; i < WV; ++i) {
-      const int e = base + i * 256 + threadIdx.x;
+      int o = i * Cfg::kThreads + threadIdx.x;
+      if (!kWholeW && o > Cfg::kChunkVec - 1) o = Cfg::kChunkVec - 1;   // surplus threads repeat the last word
+      const int e = base + o;
       wst[i] = Wp[e < wlim ? e : wlim];
     }
   };
   auto store_w = [&](int buf) {
 #pragma unroll
-    for (int i = 0; i < WV; ++i) lds[buf * Cfg::kChunkVec + i * 256 + threadIdx.x] = wst[i];
+    for (int i = 0; i < WV; ++i) {
+      int o = i * Cfg::kThreads + threadIdx.x;
+      if (!kWholeW && o > Cfg::kChunkVec - 1) o = Cfg::kChunkVec - 1;
+      lds[buf * Cfg::kChunkVec + o] = wst[i];
+    }
   };
   // `tail`: the chunk may run past the last K step; such steps get a zero A tile
   auto compute = [&](const u32x4 (&av)[TG][KC], int buf, int c, auto tail) {
@@ -1510,6 +1515,7 @@ int proj_ksplit(const mhcl_desc &d) {
   if (!fast_path_ok(d)) return 1;
   const int M = res_logits(d) + 2 * d.n;
   int kc = 4, tok = 128;
+  const int want = 256;   // one block per CU
   (void)dispatch_nt_proj(logit_tiles(M), [&](auto nt) {
     kc = ProjCfg<decltype(nt)::value>::KC;
     tok = ProjCfg<decltype(nt)::value>::kTokens;
@@ -1517,8 +1523,8 @@ int proj_ksplit(const mhcl_desc &d) {
   });
   const int nsteps = d.n * d.C / 32;
   const int64_t blocks = (d.T + tok - 1) / tok;
-  int ks = 1;   // enough blocks for two per CU, each part a whole number of chunk pairs
-  while (ks < kMaxKSplit && blocks * ks < 512 && nsteps % (ks * 2 * 2 * kc) == 0) ks *= 2;
+  int ks = 1;   // enough blocks for one per CU, each part a whole number of chunk pairs
+  while (ks < kMaxKSplit && blocks * ks < want && nsteps % (ks * 2 * 2 * kc) == 0) ks *= 2;
   return ks;
 }
 
@@ -1536,7 +1542,8 @@ hipError_t launch_proj_mfma(const mhcl_desc &d, int M, const void *x, const void
       if (e != hipSuccess) return e;
     }
     constexpr int kTok = ProjCfg<NT>::kTokens;
-    hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>((d.T + kTok - 1) / kTok), ks), dim3(256),
+    hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>((d.T + kTok - 1) / kTok), ks),
+                       dim3(ProjCfg<NT>::kThreads),
                        lds, s, static_cast<const uint16_t *>(x), static_cast<const u32x4 *>(Wp), K,
                        M, d.T, u_raw, sumsq);
     return hipGetLastError();
