@@ -46,15 +46,14 @@ def stage_bytes(stage: int, n: int, C: int, T: int, e: int) -> int:
 # kernel's readings; profiles/n4_c4096_bench_step.md), valid only for the kernel sources whose
 # digest is recorded with them: {workload: (csrc digest, {stage: bytes})}
 MEASURED_TRAFFIC = {
-    "n4_c4096": ("0c7b36747d84deae", {
-        1: int(1067.1 * 2**20 + 8.3 * 2**20),
+    "n4_c4096": ("9c6c0b8177590db0", {
+        1: int(1041.1 * 2**20 + 4.1 * 2**20),
         2: int(1028.0 * 2**20 + 256.0 * 2**20),
         3: int(1292.3 * 2**20 + 1024.0 * 2**20),
-        4: int(2615.0 * 2**20 + 7.1 * 2**20),
-        5: int(2425.8 * 2**20 + 1296.2 * 2**20),
+        4: int(2692.3 * 2**20 + 7.1 * 2**20),
+        5: int(2426.0 * 2**20 + 1296.2 * 2**20),
     }),
 }
-
 
 def csrc_digest() -> str:
     import hashlib
