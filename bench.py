@@ -168,6 +168,10 @@ def main():
     wl = si.WORKLOADS[args.workload]
     torch.cuda.set_device(0)
     inp = si.make_inputs(wl, seed=0, device="cuda:0")
+    # the layer's stream tensors sit where the package's allocator puts them (layer.py)
+    inp["x"] = mhcl.place_stream(inp["x"], mhcl.layer.PHASE_X)
+    if "g_xout" in inp:
+        inp["g_xout"] = mhcl.place_stream(inp["g_xout"], mhcl.layer.PHASE_G_XOUT)
     fwd_only = not wl.backward      # a forward-only workload times the two forward calls alone
     d = mhcl.desc_for(wl, perm=inp.get("perm"))
     L = mhcl.GpuLayer(d, inp)

@@ -11,5 +11,5 @@ from .binding import (  # noqa: F401
     mhcl_coeffs, mhcl_pre, mhcl_post, mhcl_fwd_coeffs_pre, mhcl_post_bwd, mhcl_pre_bwd,
     mhcl_coeffs_bwd, mhcl_bwd_fused, mhcl_logits, mhcl_ds_chain,
 )
-from .layer import GpuLayer, desc_for  # noqa: F401,E402
+from .layer import GpuLayer, desc_for, empty_stream, place_stream  # noqa: F401,E402
 from .autograd import HyperConnection, HyperConnectionStack, init_params  # noqa: F401,E402

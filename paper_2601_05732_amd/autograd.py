@@ -34,14 +34,16 @@ import math
 import torch
 
 from . import binding as mhcl
+from .layer import PHASE_G_X, PHASE_G_XOUT, PHASE_X, empty_stream
 
 
 class _Link:
     """What the post node leaves for the coefficient node of the same layer."""
-    __slots__ = ("y", "g_xout", "H_pre", "ws")
+    __slots__ = ("y", "g_xout", "H_pre", "ws", "g_x_phase")
 
-    def __init__(self):
+    def __init__(self, g_x_phase=PHASE_G_X):
         self.y = self.g_xout = self.H_pre = self.ws = None
+        self.g_x_phase = g_x_phase
 
 
 def _desc(x, res_mode, sk_iters, eps):
@@ -78,7 +80,7 @@ class _CoeffsPre(torch.autograd.Function):
         g_xout = link.g_xout if link.g_xout is not None else torch.zeros_like(x)
         g_h = torch.zeros(T, C, device=x.device, dtype=x.dtype) if g_h is None else g_h.contiguous()
         f = torch.float32
-        g_x = torch.empty_like(x)
+        g_x = empty_stream(x.shape, x.dtype, x.device, link.g_x_phase)
         g_y = torch.empty(T, C, device=x.device, dtype=x.dtype)     # recomputed by the fused kernel; unused
         g_W, g_b = torch.empty_like(W, dtype=f), torch.empty_like(b, dtype=f)
         g_alpha = torch.empty(3, device=x.device, dtype=f)
@@ -93,7 +95,7 @@ class _Post(torch.autograd.Function):
     def forward(ctx, x, y, H_res, H_post, link, res_mode, sk_iters, eps):
         d = _desc(x, res_mode, sk_iters, eps)
         y = y.contiguous()
-        x_out = torch.empty_like(x)
+        x_out = empty_stream(x.shape, x.dtype, x.device, PHASE_X)
         mhcl.mhcl_post(d, x, y, H_res, H_post, x_out)
         ctx.save_for_backward(H_res, H_post)
         ctx.link, ctx.d = link, d
@@ -133,9 +135,12 @@ class HyperConnection(torch.nn.Module):
     """One layer: ``x_out = H_res x + H_post^T f(H_pre x)`` on ``x [T, n, C]``."""
 
     def __init__(self, n: int, C: int, res_mode: str = "lite", sk_iters: int = 20, eps: float = 1e-6,
-                 one_index: int = 0, device="cuda"):
+                 one_index: int = 0, device="cuda", layer_index: int = 0):
         super().__init__()
         self.n, self.C = n, C
+        # g_x of this layer is g_xout of the one below: alternate the two gradient phases
+        # so that x, g_xout and g_x of a layer all differ (see layer.empty_stream)
+        self.g_x_phase = PHASE_G_X if layer_index % 2 == 0 else PHASE_G_XOUT
         self.res_mode = mhcl.RES_LITE if res_mode == "lite" else mhcl.RES_SK
         self.sk_iters, self.eps = sk_iters, eps
         W, b, alpha = init_params(n, C, self.res_mode, one_index, device)
@@ -145,7 +150,7 @@ class HyperConnection(torch.nn.Module):
         if x.dim() != 3 or x.shape[1] != self.n or x.shape[2] != self.C:
             raise ValueError(f"x must be [T, {self.n}, {self.C}], got {tuple(x.shape)}")
         x = x.contiguous()
-        link = _Link()
+        link = _Link(self.g_x_phase)
         cfg = (self.res_mode, self.sk_iters, self.eps)
         h, H_res, H_post, _ = _CoeffsPre.apply(x, self.W, self.b, self.alpha, link, *cfg)
         y = f(h)
@@ -163,7 +168,7 @@ class HyperConnectionStack(torch.nn.Module):
         self.fs = list(fs)
         self.mods = torch.nn.ModuleList([f for f in self.fs if isinstance(f, torch.nn.Module)])
         self.layers = torch.nn.ModuleList(
-            [HyperConnection(n, C, res_mode, one_index=l % n, device=device, **kw)
+            [HyperConnection(n, C, res_mode, one_index=l % n, device=device, layer_index=l, **kw)
              for l in range(len(self.fs))])
 
     def forward(self, x0: torch.Tensor):
