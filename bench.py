@@ -47,11 +47,11 @@ def stage_bytes(stage: int, n: int, C: int, T: int, e: int) -> int:
 # digest is recorded with them: {workload: (csrc digest, {stage: bytes})}
 MEASURED_TRAFFIC = {
     "n4_c4096": ("9c6c0b8177590db0", {
-        1: int(1041.1 * 2**20 + 4.1 * 2**20),
+        1: int(1040.8 * 2**20 + 4.1 * 2**20),
         2: int(1028.0 * 2**20 + 256.0 * 2**20),
         3: int(1292.3 * 2**20 + 1024.0 * 2**20),
-        4: int(2692.3 * 2**20 + 7.1 * 2**20),
-        5: int(2426.0 * 2**20 + 1296.2 * 2**20),
+        4: int(2691.1 * 2**20 + 7.1 * 2**20),
+        5: int(2433.5 * 2**20 + 1296.2 * 2**20),
     }),
 }
 
