@@ -127,8 +127,8 @@ hipError_t run_projection(const mhcl_desc &d, const void *x, const float *W, flo
 hipError_t run_coeffs_epilogue(const mhcl_desc &d, const float *u_raw, const float *sumsq,
                                const float *b, const float *alpha, float *H_res, float *H_pre,
                                float *H_post, hipStream_t s) {
-  if (d.res_mode == MHCL_RES_SUBSET)
-    return launch_coeffs_subset(d, proj_ksplit(d), u_raw, sumsq, b, alpha, H_res, H_pre, H_post, s);
+  if (coeffs_group_ok(d))
+    return launch_coeffs_group(d, proj_ksplit(d), u_raw, sumsq, b, alpha, H_res, H_pre, H_post, s);
   return launch_coeffs_epilogue(d, proj_ksplit(d), u_raw, sumsq, b, alpha, H_res, H_pre, H_post, s);
 }
 hipError_t run_coeffs_bwd_epilogue(const mhcl_desc &d, const float *u_raw, const float *sumsq,
@@ -403,8 +403,8 @@ int mhcl_bwd_fused(const mhcl_desc *desc, const void *x, const void *y, const fl
         MHCL_HIP(launch_bwd_reduce(*desc, M, x, y, g_xout, g_h, f, s));
       }
     }
-    if (desc->res_mode == MHCL_RES_SUBSET)
-      MHCL_HIP(launch_bwd_epilogue_subset_fast(*desc, b, alpha, f, s));
+    if (coeffs_group_ok(*desc))
+      MHCL_HIP(launch_bwd_epilogue_group(*desc, b, alpha, f, s));
     else
       MHCL_HIP(launch_bwd_epilogue_fast(*desc, b, alpha, f, s));
     if (wide) {

@@ -1728,7 +1728,8 @@ hipError_t launch_bwd_epilogue_fast(const mhcl_desc &d, const float *b, const fl
     case 2: return lite ? go(std::integral_constant<int, 2>{}, L{}) : go(std::integral_constant<int, 2>{}, S{});
     case 3: return lite ? go(std::integral_constant<int, 3>{}, L{}) : go(std::integral_constant<int, 3>{}, S{});
     case 4: return lite ? go(std::integral_constant<int, 4>{}, L{}) : go(std::integral_constant<int, 4>{}, S{});
-    case 5: return lite ? go(std::integral_constant<int, 5>{}, L{}) : go(std::integral_constant<int, 5>{}, S{});
+    // the full permutation form at n = 5 (120 permutations) takes the eight-lanes-per-token kernel
+    case 5: return lite ? hipErrorInvalidValue : go(std::integral_constant<int, 5>{}, S{});
   }
   return hipErrorInvalidValue;
 }

@@ -83,9 +83,11 @@ hipError_t launch_param_sums_rows(int64_t rows, int M, const float *src, float *
                                   float *g_alpha, float *part, hipStream_t s);
 
 // ---- permutation-subset form (run-time table d.perm, n up to 8) --------------
-hipError_t launch_coeffs_subset(const mhcl_desc &d, int parts, const float *u_raw,
-                                const float *sumsq, const float *b, const float *alpha,
-                                float *H_res, float *H_pre, float *H_post, hipStream_t s);
+// eight lanes per token: permutation subsets and the full form at n = 5
+bool coeffs_group_ok(const mhcl_desc &d);
+hipError_t launch_coeffs_group(const mhcl_desc &d, int parts, const float *u_raw,
+                               const float *sumsq, const float *b, const float *alpha,
+                               float *H_res, float *H_pre, float *H_post, hipStream_t s);
 hipError_t launch_coeffs_bwd_subset(const mhcl_desc &d, int parts, const float *u_raw,
                                     const float *sumsq, const float *b, const float *alpha,
                                     const float *g_H_res, const float *g_H_pre,
@@ -134,8 +136,8 @@ hipError_t launch_bwd_dots_fast(const mhcl_desc &d, const void *x, const void *y
 hipError_t launch_bwd_epilogue_fast(const mhcl_desc &d, const float *b, const float *alpha,
                                     const FastBwdWs &w, hipStream_t s);
 // the same stage for the permutation-subset form (run-time table)
-hipError_t launch_bwd_epilogue_subset_fast(const mhcl_desc &d, const float *b, const float *alpha,
-                                           const FastBwdWs &w, hipStream_t s);
+hipError_t launch_bwd_epilogue_group(const mhcl_desc &d, const float *b, const float *alpha,
+                                     const FastBwdWs &w, hipStream_t s);
 hipError_t launch_bwd_out_wide(const mhcl_desc &d, int M, const void *x, const void *g_xout,
                                const void *g_h, const FastBwdWs &w, void *g_x, void *g_y,
                                hipStream_t s);
