@@ -979,27 +979,41 @@ __global__ __launch_bounds__(256, 2) void wv_kernel(const u32x4 *__restrict__ Wa
 }
 
 // Pass 2 of the wide case in one kernel, for slices that fit on chip when W is kept
-// as ONE 16-bit part (n = 5: 100 KiB per 64-column step; the bf16 pair would be 200):
+// as ONE 16-bit part (n = 5, 130 logits: 100 KiB per 64-column step; the bf16 pair would be 200):
 //   g_x[j] = sum_i H_res[i][j] g_xout[i] + H_pre[j] g_h + (W16 vr)[j] - x[j] coefx
 //   g_y    = sum_i H_post[i] g_xout[i]
 // W16 = fp16(W) (11 significant bits; |W| must stay below 65504, weights are O(1) or
 // less), and vr enters as fp16 hi + lo parts of vr / s with the token's own scale s
-// (bwd_epilogue_fast_kernel, F16ROWS), so gradients of any magnitude fit; the MFMA
+// (F16ROWS of the per-token stage), so gradients of any magnitude fit; the MFMA
 // result is multiplied by s.  Rounding W to fp16 changes (W vr) by about 2^-12 of its
 // size, far below the rounding of g_x to bf16 that follows.  Nothing is written between
 // the passes (the two-kernel variant stores W vr as fp32 [T, nC] and reads it back).
 // One block of eight waves per CU, each wave 16 tokens per iteration; lane ownership
 // as in bwd_out_gw_kernel.
+// The per-token coefficient record (n^2 + 2n + 2 floats, 82 at n = 8) does not fit the
+// registers next to the stream tiles, so each wave parks the records of its 16 tokens
+// in its own LDS region and reads the column of H_res it needs stream by stream.
+// LDS: N x MS x 4 KiB of W16 plus 8 x 16 x (CP + 4) floats; the launcher falls back to
+// the two-kernel form when that exceeds 160 KiB.
 template <int N, int MS>
-__global__ __launch_bounds__(512, 1) void bwd_out_whi_kernel(
+struct OutW16Cfg {
+  static constexpr int kStreamVec = 4 * MS * 64;
+  static constexpr int CP = (N * N + 2 * N + 2 + 7) / 8 * 8;   // as FastBwdWs::CP
+  static constexpr int CPS = CP + 4;                           // LDS row stride (floats)
+  static constexpr int kLdsBytes = N * kStreamVec * 16 + 8 * 16 * CPS * 4;
+  static constexpr bool kFits = kLdsBytes <= 160 * 1024;
+};
+
+template <int N, int MS>
+__global__ __launch_bounds__(512, 1) void bwd_out_w16_kernel(
     const uint16_t *__restrict__ x, const uint16_t *__restrict__ g,
     const uint16_t *__restrict__ gh, const u32x4 *__restrict__ Wa, const float *__restrict__ cpk,
     const uint16_t *__restrict__ vr_hi, const uint16_t *__restrict__ vr_lo, int MP32, int C,
-    int64_t T, int tokens_per_block, int CP, uint16_t *__restrict__ g_x,
-    uint16_t *__restrict__ g_y) {
-  constexpr int NCP = N * N + 2 * N + 2;
-  constexpr int NCP4 = (NCP + 3) / 4;
-  constexpr int kStreamVec = 4 * MS * 64;       // 16-byte words of W16 per stream and 64-column step
+    int64_t T, int tokens_per_block, uint16_t *__restrict__ g_x, uint16_t *__restrict__ g_y) {
+  using Cfg = OutW16Cfg<N, MS>;
+  constexpr int NN = N * N, CP = Cfg::CP, CPS = Cfg::CPS, CP4 = CP / 4;
+  constexpr int kStreamVec = Cfg::kStreamVec;
+  constexpr int NV = (16 * CP4 + 63) / 64;     // float4 of the records each lane fetches
   extern __shared__ u32x4 lds[];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int r = lane & 15, q = lane >> 4;
@@ -1013,6 +1027,8 @@ __global__ __launch_bounds__(512, 1) void bwd_out_whi_kernel(
   }
   __syncthreads();
   const u32x4 *wl = lds + lane;
+  float *cps = reinterpret_cast<float *>(lds + N * kStreamVec) + wave * 16 * CPS;   // this wave's records
+  const float *cpr = cps + r * CPS;                                                 // this lane's token
 
   const int64_t tb = static_cast<int64_t>(blockIdx.y) * tokens_per_block;   // multiple of 128
   int64_t te = tb + tokens_per_block;
@@ -1034,7 +1050,7 @@ __global__ __launch_bounds__(512, 1) void bwd_out_whi_kernel(
     const bool live = t < te;
     const int64_t tl = live ? t : te - 1;
     u32x4 X[N][2], G[N][2], H[2], vbh[MS], vbl[MS];
-    float4 cp4[NCP4];
+    float4 rec[NV];
 #pragma unroll
     for (int j = 0; j < N; ++j)
 #pragma unroll
@@ -1049,75 +1065,145 @@ __global__ __launch_bounds__(512, 1) void bwd_out_whi_kernel(
       vbh[ms] = *reinterpret_cast<const u32x4 *>(vr_hi + tl * MP32 + ms * 32 + q * 8);
       vbl[ms] = *reinterpret_cast<const u32x4 *>(vr_lo + tl * MP32 + ms * 32 + q * 8);
     }
-    const float4 *cpp = reinterpret_cast<const float4 *>(cpk + tl * CP);
+    // the 16 records of the wave's tokens, CP4 float4 each, spread over the lanes
 #pragma unroll
-    for (int e = 0; e < NCP4; ++e) cp4[e] = cpp[e];
-    float cp[NCP4 * 4];
-#pragma unroll
-    for (int e = 0; e < NCP4; ++e) {
-      cp[4 * e] = cp4[e].x; cp[4 * e + 1] = cp4[e].y; cp[4 * e + 2] = cp4[e].z; cp[4 * e + 3] = cp4[e].w;
+    for (int i = 0; i < NV; ++i) {
+      int idx = lane + 64 * i;
+      if (idx > 16 * CP4 - 1) idx = 16 * CP4 - 1;   // surplus lanes repeat the last piece
+      const int tk = idx / CP4, part = idx - tk * CP4;
+      int64_t tt = t0 + tk;
+      if (tt > te - 1) tt = te - 1;
+      rec[i] = *reinterpret_cast<const float4 *>(cpk + tt * CP + 4 * part);
     }
-    const float cx = cp[N * N + 2 * N], vscale = cp[N * N + 2 * N + 1];
-    // Stream by stream, both 64-byte halves of a line computed and stored together; the
-    // g_xout and g_h tiles stay packed and are unpacked at each use (registers).
-    {   // g_y
-      u32x4 ov[2];
+    __builtin_amdgcn_wave_barrier();   // (LDS requests of a wave are served in order)
 #pragma unroll
-      for (int u = 0; u < 2; ++u) {
-        float o[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) o[e] = 0.f;
-#pragma unroll
-        for (int i = 0; i < N; ++i) {
-          float gv[8];
-          unpack(G[i][u], gv);
-#pragma unroll
-          for (int e = 0; e < 8; ++e) o[e] += cp[N * N + N + i] * gv[e];
-        }
-        ov[u] = pack(o);
-      }
-      if (live) {
-        *reinterpret_cast<u32x4 *>(g_y + t * C + c0) = ov[0];
-        *reinterpret_cast<u32x4 *>(g_y + t * C + c0 + 32) = ov[1];
-      }
+    for (int i = 0; i < NV; ++i) {
+      int idx = lane + 64 * i;
+      if (idx > 16 * CP4 - 1) idx = 16 * CP4 - 1;
+      const int tk = idx / CP4, part = idx - tk * CP4;
+      *reinterpret_cast<float4 *>(cps + tk * CPS + 4 * part) = rec[i];
     }
+    __builtin_amdgcn_wave_barrier();
+    const float cx = cpr[NN + 2 * N], vscale = cpr[NN + 2 * N + 1];
+    float hq[N];
 #pragma unroll
-    for (int j = 0; j < N; ++j) {
-      u32x4 ov[2];
+    for (int i = 0; i < N; ++i) hq[i] = cpr[NN + N + i];
+    if constexpr (N <= 5) {
+      // Stream by stream, both 64-byte halves of a line computed and stored together; the
+      // g_xout and g_h tiles stay packed and are unpacked at each use (registers).
+      {   // g_y
+        u32x4 ov[2];
 #pragma unroll
-      for (int u = 0; u < 2; ++u) {
-        f32x4 wv[2];
+        for (int u = 0; u < 2; ++u) {
+          float o[8];
 #pragma unroll
-        for (int hh = 0; hh < 2; ++hh) {
-          const int h = 2 * u + hh;
-          wv[hh] = f32x4{0.f, 0.f, 0.f, 0.f};
+          for (int e = 0; e < 8; ++e) o[e] = 0.f;
 #pragma unroll
-          for (int ms = 0; ms < MS; ++ms) {
-            const u32x4 wh = wl[((j * 4 + h) * MS + ms) * 64];
-            wv[hh] = mfma16h(wh, vbh[ms], wv[hh]);
-            wv[hh] = mfma16h(wh, vbl[ms], wv[hh]);
+          for (int i = 0; i < N; ++i) {
+            float gv[8];
+            unpack(G[i][u], gv);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[e] += hq[i] * gv[e];
           }
+          ov[u] = pack(o);
         }
-        float xv[8], hv[8], o[8];
-        unpack(X[j][u], xv);
+        if (live) {
+          *reinterpret_cast<u32x4 *>(g_y + t * C + c0) = ov[0];
+          *reinterpret_cast<u32x4 *>(g_y + t * C + c0 + 32) = ov[1];
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < N; ++j) {
+        float hr[N];
+#pragma unroll
+        for (int i = 0; i < N; ++i) hr[i] = cpr[i * N + j];
+        const float hp = cpr[NN + j];
+        u32x4 ov[2];
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+          f32x4 wv[2];
+#pragma unroll
+          for (int hh = 0; hh < 2; ++hh) {
+            const int h = 2 * u + hh;
+            wv[hh] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ms = 0; ms < MS; ++ms) {
+              const u32x4 wh = wl[((j * 4 + h) * MS + ms) * 64];
+              wv[hh] = mfma16h(wh, vbh[ms], wv[hh]);
+              wv[hh] = mfma16h(wh, vbl[ms], wv[hh]);
+            }
+          }
+          float xv[8], hv[8], o[8];
+          unpack(X[j][u], xv);
+          unpack(H[u], hv);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) o[e] = vscale * wv[e >> 2][e & 3] - xv[e] * cx + hp * hv[e];
+#pragma unroll
+          for (int i = 0; i < N; ++i) {
+            float gv[8];
+            unpack(G[i][u], gv);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[e] += hr[i] * gv[e];
+          }
+          ov[u] = pack(o);
+        }
+        if (live) {
+          *reinterpret_cast<u32x4 *>(g_x + (t * N + j) * C + c0) = ov[0];
+          *reinterpret_cast<u32x4 *>(g_x + (t * N + j) * C + c0 + 32) = ov[1];
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    } else {
+      // One 64-byte half of the lines at a time: the g_xout tile of that half is unpacked
+      // once and serves g_y and all n output streams (unpacking per stream made the kernel
+      // ALU bound at n = 8).
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        float gv[N][8], hv[8];
+#pragma unroll
+        for (int i = 0; i < N; ++i) unpack(G[i][u], gv[i]);
         unpack(H[u], hv);
+        {   // g_y
+          float o[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) o[e] = vscale * wv[e >> 2][e & 3] - xv[e] * cx + cp[N * N + j] * hv[e];
+          for (int e = 0; e < 8; ++e) o[e] = 0.f;
 #pragma unroll
-        for (int i = 0; i < N; ++i) {
-          float gv[8];
-          unpack(G[i][u], gv);
+          for (int i = 0; i < N; ++i)
 #pragma unroll
-          for (int e = 0; e < 8; ++e) o[e] += cp[i * N + j] * gv[e];
+            for (int e = 0; e < 8; ++e) o[e] += hq[i] * gv[i][e];
+          if (live) *reinterpret_cast<u32x4 *>(g_y + t * C + c0 + 32 * u) = pack(o);
         }
-        ov[u] = pack(o);
+#pragma unroll
+        for (int j = 0; j < N; ++j) {
+          f32x4 wv[2];
+#pragma unroll
+          for (int hh = 0; hh < 2; ++hh) {
+            const int h = 2 * u + hh;
+            wv[hh] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ms = 0; ms < MS; ++ms) {
+              const u32x4 wh = wl[((j * 4 + h) * MS + ms) * 64];
+              wv[hh] = mfma16h(wh, vbh[ms], wv[hh]);
+              wv[hh] = mfma16h(wh, vbl[ms], wv[hh]);
+            }
+          }
+          const float hp = cpr[NN + j];
+          float xv[8], o[8];
+          unpack(X[j][u], xv);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) o[e] = vscale * wv[e >> 2][e & 3] - xv[e] * cx + hp * hv[e];
+#pragma unroll
+          for (int i = 0; i < N; ++i) {
+            const float hr = cpr[i * N + j];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[e] += hr * gv[i][e];
+          }
+          if (live) *reinterpret_cast<u32x4 *>(g_x + (t * N + j) * C + c0 + 32 * u) = pack(o);
+          __builtin_amdgcn_sched_barrier(0);
+        }
       }
-      if (live) {
-        *reinterpret_cast<u32x4 *>(g_x + (t * N + j) * C + c0) = ov[0];
-        *reinterpret_cast<u32x4 *>(g_x + (t * N + j) * C + c0 + 32) = ov[1];
-      }
-      __builtin_amdgcn_sched_barrier(0);
     }
+    __builtin_amdgcn_wave_barrier();   // the records are overwritten in the next iteration
   }
 }
 
@@ -1558,7 +1644,12 @@ bool fast_bwd_ok(const mhcl_desc &d) { return fast_path_ok(d); }
 // n <= 4; everything else (n >= 5, any permutation subset) takes the wide pass 2
 bool fast_bwd_wide(const mhcl_desc &d) { return d.n > 4 || d.res_mode == MHCL_RES_SUBSET; }
 // n = 5 of the full forms: wide pass 2 in one kernel with W as one fp16 part in LDS
-bool fast_bwd_whi(const mhcl_desc &d) { return d.n == 5 && d.res_mode != MHCL_RES_SUBSET; }
+bool fast_bwd_whi(const mhcl_desc &d) {
+  if (!fast_bwd_wide(d) || d.n < 5) return false;
+  const int MS = logit_steps(res_logits(d) + 2 * d.n);
+  const int CP = (d.n * d.n + 2 * d.n + 2 + 7) / 8 * 8;
+  return d.n * MS * 4096 + 8 * 16 * (CP + 4) * 4 <= 160 * 1024;   // OutW16Cfg::kLdsBytes
+}
 
 namespace {
 // K steps per wave of bwd_gw_kernel: bounded by its accumulators (2 * NT * 4 registers per step)
@@ -1640,7 +1731,7 @@ hipError_t launch_pack_w_ab(const mhcl_desc &d, int M, const float *W, void *Wp,
   const int K = d.n * d.C, NT = logit_tiles(M), MS = logit_steps(M);
   const int nb_b = ((K / 32) * NT * 64 + 255) / 256;
   const int nb_a = ((K / 64) * 4 * MS * 64 + 255) / 256;
-  // one fp16 part where the only reader is bwd_out_whi_kernel
+  // one fp16 part where the only reader is bwd_out_w16_kernel
   hipLaunchKernelGGL(pack_w_ab_kernel, dim3(nb_b + nb_a), dim3(256), 0, s, W, K, M, NT, MS, nb_b,
                      fast_bwd_whi(d) ? 1 : 0, static_cast<uint4 *>(Wp), static_cast<uint4 *>(Wa));
   return hipGetLastError();
@@ -1712,7 +1803,7 @@ hipError_t launch_bwd_epilogue_fast(const mhcl_desc &d, const float *b, const fl
     constexpr int N = decltype(nn)::value, MODE = decltype(mm)::value;
     if (w.MP32 != (Dims<N, MODE>::M + 31) / 32 * 32 || w.MP16 != (Dims<N, MODE>::M + 15) / 16 * 16)
       return hipErrorInvalidValue;
-    constexpr bool kF16 = N == 5;   // the widths of fast_bwd_whi(): rows for bwd_out_whi_kernel
+    constexpr bool kF16 = N == 5;   // the widths of fast_bwd_whi(): rows for bwd_out_w16_kernel
     if (kF16 != fast_bwd_whi(d) || (kF16 && w.CP < N * N + 2 * N + 2)) return hipErrorInvalidValue;
     hipLaunchKernelGGL((bwd_epilogue_fast_kernel<N, MODE, kF16>),
                        dim3(static_cast<unsigned>(Tpad / 64)), dim3(64), 0, s, w.u_raw, w.sumsq,
@@ -1770,7 +1861,6 @@ hipError_t launch_bwd_out_wide(const mhcl_desc &d, int M, const void *x, const v
                                hipStream_t s) {
   const int K = d.n * d.C, MS = logit_steps(M);
   if (fast_bwd_whi(d)) {
-    if (MS != 2 && MS != 5) return hipErrorInvalidValue;
     // one kernel, W as one fp16 part resident in LDS; one round of one block per CU
     const int64_t xb = d.C / 64;
     int64_t chunks = 256 / xb;
@@ -1779,23 +1869,45 @@ hipError_t launch_bwd_out_wide(const mhcl_desc &d, int M, const void *x, const v
     if (tpb1 < 256) tpb1 = 256;
     while ((d.T + tpb1 - 1) / tpb1 > 32768) tpb1 *= 2;
     const dim3 grid1(static_cast<unsigned>(xb), static_cast<unsigned>((d.T + tpb1 - 1) / tpb1));
-    auto fused = [&](auto ms) {
-      constexpr int kMS = decltype(ms)::value;
-      constexpr int lds = 5 * 4 * kMS * 64 * 16;
-      auto kern = bwd_out_whi_kernel<5, kMS>;
-      if (lds > 64 * 1024) {
-        hipError_t e1 = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-        if (e1 != hipSuccess) return e1;
+    auto fused = [&](auto nn, auto ms) {
+      constexpr int kN = decltype(nn)::value, kMS = decltype(ms)::value;
+      using Cfg = OutW16Cfg<kN, kMS>;
+      if constexpr (!Cfg::kFits) {
+        return hipErrorInvalidValue;
+      } else {
+        if (w.CP != Cfg::CP) return hipErrorInvalidValue;
+        auto kern = bwd_out_w16_kernel<kN, kMS>;
+        if (Cfg::kLdsBytes > 64 * 1024) {
+          hipError_t e1 = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                              hipFuncAttributeMaxDynamicSharedMemorySize,
+                                              Cfg::kLdsBytes);
+          if (e1 != hipSuccess) return e1;
+        }
+        hipLaunchKernelGGL(kern, grid1, dim3(512), Cfg::kLdsBytes, s,
+                           static_cast<const uint16_t *>(x), static_cast<const uint16_t *>(g_xout),
+                           static_cast<const uint16_t *>(g_h), reinterpret_cast<const u32x4 *>(w.Wa),
+                           w.cpk, w.vr_hi, w.vr_lo, w.MP32, d.C, d.T, static_cast<int>(tpb1),
+                           static_cast<uint16_t *>(g_x), static_cast<uint16_t *>(g_y));
+        return hipGetLastError();
       }
-      hipLaunchKernelGGL(kern, grid1, dim3(512), lds, s, static_cast<const uint16_t *>(x),
-                         static_cast<const uint16_t *>(g_xout), static_cast<const uint16_t *>(g_h),
-                         reinterpret_cast<const u32x4 *>(w.Wa), w.cpk, w.vr_hi, w.vr_lo, w.MP32, d.C,
-                         d.T, static_cast<int>(tpb1), w.CP, static_cast<uint16_t *>(g_x),
-                         static_cast<uint16_t *>(g_y));
-      return hipGetLastError();
     };
-    return MS == 2 ? fused(std::integral_constant<int, 2>{}) : fused(std::integral_constant<int, 5>{});
+    auto by_ms = [&](auto nn) {
+      switch (MS) {
+        case 1: return fused(nn, std::integral_constant<int, 1>{});
+        case 2: return fused(nn, std::integral_constant<int, 2>{});
+        case 3: return fused(nn, std::integral_constant<int, 3>{});
+        case 4: return fused(nn, std::integral_constant<int, 4>{});
+        case 5: return fused(nn, std::integral_constant<int, 5>{});
+      }
+      return hipErrorInvalidValue;
+    };
+    switch (d.n) {
+      case 5: return by_ms(std::integral_constant<int, 5>{});
+      case 6: return by_ms(std::integral_constant<int, 6>{});
+      case 7: return by_ms(std::integral_constant<int, 7>{});
+      case 8: return by_ms(std::integral_constant<int, 8>{});
+    }
+    return hipErrorInvalidValue;
   }
   // 1024 tokens per block, more once that would exceed the grid's second dimension
   int64_t tpb = 1024;

@@ -114,7 +114,7 @@ hipError_t launch_proj_mfma(const mhcl_desc &d, int M, const void *x, const void
 
 // fused backward on the fast path (needs fast_bwd_ok(desc))
 bool fast_bwd_ok(const mhcl_desc &d);
-bool fast_bwd_whi(const mhcl_desc &d);    // n = 5, full forms: that pass 2 as one kernel (W as one fp16 part)
+bool fast_bwd_whi(const mhcl_desc &d);    // wide case, n >= 5, where W fits LDS as one fp16 part: that pass 2 as one kernel
 bool fast_bwd_wide(const mhcl_desc &d);   // n >= 5 or a subset: pass 2 split into W vr and the mixing
 int gw_chunks_fast(const mhcl_desc &d);
 struct FastBwdWs {

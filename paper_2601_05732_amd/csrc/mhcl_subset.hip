@@ -551,8 +551,8 @@ hipError_t launch_bwd_epilogue_group(const mhcl_desc &d, const float *b, const f
   const int64_t Tpad = (d.T + 63) / 64 * 64;
   const int M = g.K + 2 * d.n;
   if (w.MP32 != (M + 31) / 32 * 32 || w.MP16 != (M + 15) / 16 * 16) return hipErrorInvalidValue;
-  const bool f16 = fast_bwd_whi(d);   // rows for bwd_out_whi_kernel
-  if (f16 && (d.n != 5 || w.CP < d.n * d.n + 2 * d.n + 2)) return hipErrorInvalidValue;
+  const bool f16 = fast_bwd_whi(d);   // rows for bwd_out_w16_kernel
+  if (f16 && w.CP < d.n * d.n + 2 * d.n + 2) return hipErrorInvalidValue;
   return dispatch_n8(d.n, [&](auto nn) {
     constexpr int N = decltype(nn)::value;
     auto launch = [&](auto kern) {
@@ -566,7 +566,7 @@ hipError_t launch_bwd_epilogue_group(const mhcl_desc &d, const float *b, const f
                          w.gz);
       return hipGetLastError();
     };
-    if constexpr (N == 5) {
+    if constexpr (N >= 5) {
       if (f16) return launch(coeffs_group_kernel<N, true, true>);
     }
     return launch(coeffs_group_kernel<N, true, false>);
