@@ -260,3 +260,30 @@ def test_backward_scales_exactly_with_the_upstream_gradients(n, C):
         for k, v in base.items():
             got = getattr(Ls, k).float() / sc
             assert torch.equal(got, v), (sc, k, float((got - v).abs().max()))
+
+
+# Many tokens, narrow streams: the launch shapes that depend on the token count (128-token
+# blocks of backward pass 1 from 32640 tokens on, one round of resident blocks in pass 2,
+# the K split of the projection) with a ragged tail, for stream counts and forms the
+# stated workloads do not cover at that length.  Narrow enough for the oracle to redo every token.
+LONG_CASES = [
+    _small("long_n1", n=1, C=64, T=32768 + 77),
+    _small("long_n2_sk", n=2, C=128, T=32640 + 5, res_mode="sk"),
+    _small("long_n3", n=3, C=192, T=33000),
+    _small("long_n4", n=4, C=64, T=40000 - 1),
+    _small("long_n5", n=5, C=64, T=32768 + 130),
+    si.Workload(name="long_n6_k24", n=6, C=128, T=32768 + 65, io="bf16", res_mode="subset", n_perm=24),
+]
+
+
+@pytest.mark.parametrize("wl", LONG_CASES, ids=lambda w: w.name)
+def test_many_tokens_all_compared(wl):
+    print(f"case {wl}", flush=True)
+    inp = si.make_inputs(wl, seed=11, device="cuda")
+    L = GpuLayer(desc_for(wl, perm=inp.get("perm")), inp)
+    L.forward_fused()
+    L.backward_fused()
+    torch.cuda.synchronize()
+    ref = oracle_reference(inp, wl)
+    _check_forward(L, ref, wl)
+    _check_backward(L, ref, wl)
