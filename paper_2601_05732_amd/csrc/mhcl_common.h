@@ -180,8 +180,9 @@ __device__ __forceinline__ float token_coeffs(const float *u_raw, float sumsq, i
         float s = 0.f;
 #pragma unroll
         for (int i = 0; i < N; ++i) s += H_res[i * N + j];
+        const float inv = 1.f / s;   // one division per line; the entries are scaled by its result
 #pragma unroll
-        for (int i = 0; i < N; ++i) H_res[i * N + j] = H_res[i * N + j] / s;
+        for (int i = 0; i < N; ++i) H_res[i * N + j] = H_res[i * N + j] * inv;
         if (sums) sums[(2 * it) * N + j] = s;
       }
 #pragma unroll
@@ -189,8 +190,9 @@ __device__ __forceinline__ float token_coeffs(const float *u_raw, float sumsq, i
         float s = 0.f;
 #pragma unroll
         for (int j = 0; j < N; ++j) s += H_res[i * N + j];
+        const float inv = 1.f / s;
 #pragma unroll
-        for (int j = 0; j < N; ++j) H_res[i * N + j] = H_res[i * N + j] / s;
+        for (int j = 0; j < N; ++j) H_res[i * N + j] = H_res[i * N + j] * inv;
         if (sums) sums[(2 * it + 1) * N + i] = s;
       }
     }
@@ -232,24 +234,26 @@ __device__ __forceinline__ void token_coeffs_bwd(const float *gH_res, const floa
 #pragma unroll
       for (int i = 0; i < N; ++i) {   // undo the row step
         const float s = sums[(2 * it + 1) * N + i];
+        const float inv = 1.f / s;
         float d = 0.f;
 #pragma unroll
         for (int j = 0; j < N; ++j) d += g[i * N + j] * H_res[i * N + j];
 #pragma unroll
         for (int j = 0; j < N; ++j) {
-          g[i * N + j] = (g[i * N + j] - d) / s;
+          g[i * N + j] = (g[i * N + j] - d) * inv;
           H_res[i * N + j] *= s;
         }
       }
 #pragma unroll
       for (int j = 0; j < N; ++j) {   // undo the column step
         const float s = sums[(2 * it) * N + j];
+        const float inv = 1.f / s;
         float d = 0.f;
 #pragma unroll
         for (int i = 0; i < N; ++i) d += g[i * N + j] * H_res[i * N + j];
 #pragma unroll
         for (int i = 0; i < N; ++i) {
-          g[i * N + j] = (g[i * N + j] - d) / s;
+          g[i * N + j] = (g[i * N + j] - d) * inv;
           H_res[i * N + j] *= s;
         }
       }
