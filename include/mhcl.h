@@ -179,10 +179,11 @@ int mhcl_coeffs_bwd(const mhcl_desc *desc, const void *x, const float *W, const 
  * in : x, y, W, b, alpha as in forward; g_xout [T,n,C], g_h [T,C] io
  * out: g_x [T,n,C], g_y [T,C] io; g_W [nC,M], g_b [M], g_alpha [3] f32; all
  *      overwritten.
- * For n = 5 with bf16 streams (full permutation or SK form) the product W vr
- * inside g_x uses W rounded to fp16 (11 significant bits; the change is far
- * below the bf16 rounding of g_x): entries of W must stay below 65504 in
- * magnitude there. */
+ * For n >= 5 with bf16 streams and C a multiple of 64 (any form; with a
+ * permutation subset only while n * ceil(M / 32) * 4 KiB of W plus the
+ * per-token records fit the 160 KiB of LDS) the product W vr inside g_x uses
+ * W rounded to fp16 (11 significant bits; the change is far below the bf16
+ * rounding of g_x): entries of W must stay below 65504 in magnitude there. */
 int mhcl_bwd_fused(const mhcl_desc *desc, const void *x, const void *y, const float *W,
                    const float *b, const float *alpha, const void *g_xout, const void *g_h,
                    void *g_x, void *g_y, float *g_W, float *g_b, float *g_alpha,
