@@ -178,7 +178,8 @@ int mhcl_coeffs_bwd(const mhcl_desc *desc, const void *x, const float *W, const 
  * passes.  Coefficients are recomputed from x.
  * in : x, y, W, b, alpha as in forward; g_xout [T,n,C], g_h [T,C] io
  * out: g_x [T,n,C], g_y [T,C] io; g_W [nC,M], g_b [M], g_alpha [3] f32; all
- *      overwritten.
+ *      overwritten.  g_y may be NULL (a caller that needed it before g_h
+ *      existed has it already): it is then neither computed nor written.
  * For n >= 5 with bf16 streams and C a multiple of 64 (any form; with a
  * permutation subset only while n * ceil(M / 32) * 4 KiB of W plus the
  * per-token records fit the 160 KiB of LDS) the product W vr inside g_x uses

@@ -81,11 +81,11 @@ class _CoeffsPre(torch.autograd.Function):
         g_h = torch.zeros(T, C, device=x.device, dtype=x.dtype) if g_h is None else g_h.contiguous()
         f = torch.float32
         g_x = empty_stream(x.shape, x.dtype, x.device, link.g_x_phase)
-        g_y = torch.empty(T, C, device=x.device, dtype=x.dtype)     # recomputed by the fused kernel; unused
         g_W, g_b = torch.empty_like(W, dtype=f), torch.empty_like(b, dtype=f)
         g_alpha = torch.empty(3, device=x.device, dtype=f)
         ws = mhcl.new_workspace(d, mhcl.OP_BWD_FUSED, x.device)
-        mhcl.mhcl_bwd_fused(d, x, link.y, W, b, alpha, g_xout, g_h, g_x, g_y, g_W, g_b, g_alpha, ws)
+        # g_y went out through the post node already: not asked for again
+        mhcl.mhcl_bwd_fused(d, x, link.y, W, b, alpha, g_xout, g_h, g_x, None, g_W, g_b, g_alpha, ws)
         link.y = link.g_xout = None
         return g_x, g_W, g_b, g_alpha, None, None, None, None
 

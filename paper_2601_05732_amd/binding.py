@@ -246,7 +246,8 @@ def mhcl_bwd_fused(d, x, y, W, b, alpha, g_xout, g_h, g_x, g_y, g_W, g_b, g_alph
         _ptr(W, f, (d.n * d.C, d.M), "W"), _ptr(b, f, (d.M,), "b"),
         _ptr(alpha, f, (3,), "alpha"), _ptr(g_xout, io, (d.T, d.n, d.C), "g_xout"),
         _ptr(g_h, io, (d.T, d.C), "g_h"), _ptr(g_x, io, (d.T, d.n, d.C), "g_x"),
-        _ptr(g_y, io, (d.T, d.C), "g_y"), _ptr(g_W, f, (d.n * d.C, d.M), "g_W"),
+        None if g_y is None else _ptr(g_y, io, (d.T, d.C), "g_y"),
+        _ptr(g_W, f, (d.n * d.C, d.M), "g_W"),
         _ptr(g_b, f, (d.M,), "g_b"), _ptr(g_alpha, f, (3,), "g_alpha"), wp, wb, _stream()),
         "mhcl_bwd_fused")
 

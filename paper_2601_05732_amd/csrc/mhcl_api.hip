@@ -382,9 +382,9 @@ int mhcl_bwd_fused(const mhcl_desc *desc, const void *x, const void *y, const fl
     return MHCL_OK;
   }
   if (!all_ok(x, y, (const void *)W, (const void *)b, (const void *)alpha, g_xout, g_h,
-              (const void *)g_x, (const void *)g_y, (const void *)g_W, (const void *)g_b,
-              (const void *)g_alpha))
+              (const void *)g_x, (const void *)g_W, (const void *)g_b, (const void *)g_alpha))
     return MHCL_ERR_INVALID_ARG;
+  if (g_y && !aligned16(g_y)) return MHCL_ERR_INVALID_ARG;   // g_y is optional
   if (!ws || !aligned16(ws) || ws_bytes < mhcl_workspace_bytes(desc, MHCL_OP_BWD_FUSED))
     return MHCL_ERR_WORKSPACE;
   hipStream_t s = static_cast<hipStream_t>(stream);

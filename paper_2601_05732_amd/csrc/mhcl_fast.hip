@@ -791,7 +791,7 @@ __global__ __launch_bounds__(256 * SLABS, SLABS == 1 ? 2 : 1) void bwd_out_gw_ke
       for (int i = 0; i < N; ++i) unpack(in.G[i][u], gv[u][i]);
       unpack(in.H[u], hv[u]);
     }
-    {   // g_y
+    if (g_y != nullptr) {   // (optional output)
       u32x4 ov[2];
 #pragma unroll
       for (int u = 0; u < 2; ++u) {
@@ -1091,7 +1091,7 @@ __global__ __launch_bounds__(512, 1) void bwd_out_w16_kernel(
     if constexpr (N <= 5) {
       // Stream by stream, both 64-byte halves of a line computed and stored together; the
       // g_xout and g_h tiles stay packed and are unpacked at each use (registers).
-      {   // g_y
+      if (g_y != nullptr) {   // (optional output)
         u32x4 ov[2];
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
@@ -1163,7 +1163,7 @@ __global__ __launch_bounds__(512, 1) void bwd_out_w16_kernel(
 #pragma unroll
         for (int i = 0; i < N; ++i) unpack(G[i][u], gv[i]);
         unpack(H[u], hv);
-        {   // g_y
+        if (g_y != nullptr) {   // (optional output)
           float o[8];
 #pragma unroll
           for (int e = 0; e < 8; ++e) o[e] = 0.f;
@@ -1236,7 +1236,7 @@ __global__ __launch_bounds__(256) void mix_wide_kernel(
   for (int i = 0; i < N; ++i)
     unpack(*reinterpret_cast<const u32x4 *>(g + (t * N + i) * C + c), gv[i]);
   unpack(*reinterpret_cast<const u32x4 *>(gh + t * C + c), hv);
-  {
+  if (g_y != nullptr) {   // (optional output)
     float o[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) {

@@ -417,16 +417,18 @@ __global__ __launch_bounds__(kBlock) void gx_generic_kernel(
 #pragma unroll
     for (int i = 0; i < N; ++i) IO::load(g_xout, (t * N + i) * C + c, gv[i]);
     IO::load(g_h, t * C + c, gh);
-    float gy[V];
+    if (g_y != nullptr) {   // (optional output)
+      float gy[V];
 #pragma unroll
-    for (int e = 0; e < V; ++e) gy[e] = 0.f;
+      for (int e = 0; e < V; ++e) gy[e] = 0.f;
 #pragma unroll
-    for (int i = 0; i < N; ++i) {
-      const float w = o.H_post[t * N + i];
+      for (int i = 0; i < N; ++i) {
+        const float w = o.H_post[t * N + i];
 #pragma unroll
-      for (int e = 0; e < V; ++e) gy[e] += w * gv[i][e];
+        for (int e = 0; e < V; ++e) gy[e] += w * gv[i][e];
+      }
+      IO::store(g_y, t * C + c, gy);
     }
-    IO::store(g_y, t * C + c, gy);
   }
 #pragma unroll
   for (int j = 0; j < N; ++j) {

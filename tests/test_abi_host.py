@@ -70,6 +70,14 @@ def test_null_and_misaligned_pointers_fail_before_any_launch():
     assert L.mhcl_coeffs(ctypes.byref(d.c), ok, ok, ok, ok, ok, ok, ok, None, 0, None) == 3
     assert L.mhcl_coeffs(ctypes.byref(d.c), ok, ok, ok, ok, ok, ok, ok, ok, 16, None) == 3
     assert L.mhcl_bwd_fused(ctypes.byref(d.c), *([ok] * 12), None, 0, None) == 3
+    # g_y (9th tensor) is optional: NULL passes the pointer checks, a misaligned one does not
+    args = [ok] * 12
+    args[8] = None
+    assert L.mhcl_bwd_fused(ctypes.byref(d.c), *args, None, 0, None) == 3
+    args[8] = ok + 4
+    assert L.mhcl_bwd_fused(ctypes.byref(d.c), *args, None, 0, None) == 1
+    args[8], args[7] = ok, None                                              # g_x is not optional
+    assert L.mhcl_bwd_fused(ctypes.byref(d.c), *args, None, 0, None) == 1
     assert L.mhcl_coeffs(None, ok, ok, ok, ok, ok, ok, ok, ok, 1 << 20, None) == 1
     assert mhcl.lib().mhcl_status_string(3).decode().startswith("workspace")
     # diagnostics

@@ -287,3 +287,32 @@ def test_many_tokens_all_compared(wl):
     ref = oracle_reference(inp, wl)
     _check_forward(L, ref, wl)
     _check_backward(L, ref, wl)
+
+
+@pytest.mark.parametrize("wl", [_small("nogy_n4", C=256, T=333), _small("nogy_n5", n=5, C=128, T=150),
+                                _small("nogy_f32", n=3, C=40, T=19, io="f32"),
+                                si.Workload(name="nogy_n8", n=8, C=64, T=150, io="bf16",
+                                            res_mode="subset", n_perm=64),
+                                si.Workload(name="nogy_n8_k120", n=8, C=128, T=130, io="bf16",
+                                            res_mode="subset", n_perm=120)],
+                         ids=lambda w: w.name)
+def test_fused_backward_without_g_y(wl):
+    """g_y is optional in mhcl_bwd_fused: without it every other output is bit for bit
+    the same and the g_y buffer is left alone."""
+    import paper_2601_05732_amd as mhcl
+    print(f"case {wl}", flush=True)
+    inp = si.make_inputs(wl, seed=5, device="cuda")
+    L = GpuLayer(desc_for(wl, perm=inp.get("perm")), inp)
+    L.backward_fused()
+    torch.cuda.synchronize()
+    want = {k: getattr(L, k).clone() for k in ("g_x", "g_W", "g_b", "g_alpha")}
+    L.g_y.fill_(7.0)
+    for k in want:
+        getattr(L, k).zero_()
+    i = L.inp
+    mhcl.mhcl_bwd_fused(L.d, i["x"], i["y"], i["W"], i["b"], i["alpha"], i["g_xout"], i["g_h"],
+                        L.g_x, None, L.g_W, L.g_b, L.g_alpha, L.ws)
+    torch.cuda.synchronize()
+    for k, v in want.items():
+        assert torch.equal(getattr(L, k), v), k
+    assert bool((L.g_y.float() == 7.0).all())
