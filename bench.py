@@ -144,6 +144,9 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="n4_c4096")
+    ap.add_argument("--tokens", type=int, default=0,
+                    help="run the workload's shape with this many tokens instead of its own count "
+                         "(a scaling aid; the headline figure is the default)")
     ap.add_argument("--cpu-sample", type=int, default=16384)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--detail", action="store_true", help="per-stage times on stderr")
@@ -166,6 +169,9 @@ def main():
     import synth_inputs as si
 
     wl = si.WORKLOADS[args.workload]
+    if args.tokens > 0:
+        import dataclasses
+        wl = dataclasses.replace(wl, T=args.tokens)
     torch.cuda.set_device(0)
     inp = si.make_inputs(wl, seed=0, device="cuda:0")
     # the layer's stream tensors sit where the package's allocator puts them (layer.py)
@@ -268,8 +274,9 @@ def main():
     achieved = stage_bytes(dominant, wl.n, wl.C, wl.T, e) / kern_ms / 1e6
     out = {
         "metric": "tokens/s + achieved HBM GB/s, fused mHC-lite fwd+bwd, n=4 C=4096 32k tok"
-                  if args.workload == "n4_c4096" else
-                  f"tokens/s, {'forward' if fwd_only else 'fused fwd+bwd'}, {args.workload}",
+                  if args.workload == "n4_c4096" and args.tokens <= 0 else
+                  f"tokens/s, {'forward' if fwd_only else 'fused fwd+bwd'}, {args.workload}"
+                  + (f" at {wl.T} tokens" if args.tokens > 0 else ""),
         "value": tokens_per_s,
         "unit": "tokens/s",
         "n_gpus": 1,
@@ -289,7 +296,8 @@ def main():
                    "path_frac_of_peak": floor_bytes / (dt / args.steps) / 1e9 / PEAK_HBM_GBS},
         "roofline": {"bound": "hbm", "kernel": STAGES[dominant], "achieved": achieved,
                      "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": achieved / PEAK_HBM_GBS,
-                     "kernel_ms": kern_ms, "traffic": measured_traffic(args.workload, dominant)},
+                     "kernel_ms": kern_ms,
+                     "traffic": measured_traffic(args.workload, dominant) if args.tokens <= 0 else None},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(inp, wl, min(args.cpu_sample, wl.T))
