@@ -5,8 +5,8 @@ A step is one pass of the whole path over one batch of synthetic input, all
 tensors resident in HBM: mhcl_fwd_coeffs_pre, mhcl_post (the two forward calls
 around the caller's layer function) and mhcl_bwd_fused.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
-                    [--no-cpu-baseline] [--detail]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--tokens T]
+                    [--no-cpu-baseline] [--detail] [--graph] [--copy-calibration]
 """
 from __future__ import annotations
 
