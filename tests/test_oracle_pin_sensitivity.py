@@ -36,6 +36,18 @@ MUTANTS = [
      "acc += x[(size_t)t * nC + k] * v[(size_t)t * M + m];", 0),
     ("g_alpha_without_the_logit", "g_alpha[g] += g_z[(size_t)t * M + m] * uu[(size_t)t * M + m];",
      "g_alpha[g] += g_z[(size_t)t * M + m];", 0),
+    ("sk_backward_row_step_without_its_sum",
+     "for (int j = 0; j < n; ++j) g[i * n + j] = (g[i * n + j] - d) / s[i];",
+     "for (int j = 0; j < n; ++j) g[i * n + j] = g[i * n + j] / s[i];", 0),
+    ("sk_backward_column_step_divides_by_row_sums",
+     "for (int i = 0; i < n; ++i) g[i * n + j] = (g[i * n + j] - d) / s[j];",
+     "for (int i = 0; i < n; ++i) g[i * n + j] = (g[i * n + j] - d) / s[i];", 0),
+    ("sk_backward_forgets_the_exponential", "g_z[(size_t)t * M + e] = g[e] * E[e];",
+     "g_z[(size_t)t * M + e] = g[e];", 0),
+    ("relative_range_upside_down", "nu[t] = mn / mx;", "nu[t] = mx / mn;", 0),
+    ("layer_product_on_the_other_side", "s += Hl[i * n + k] * Q[k * n + j];", "s += Q[i * n + k] * Hl[k * n + j];", 0),
+    ("g_y_with_unit_gates", "acc += H_post[(size_t)t * n + i] * gt[(size_t)i * C + c];",
+     "acc += gt[(size_t)i * C + c];", 0),
     ("subset_table_read_as_inverse",
      "for (int i = 0; i < n; ++i) P[((size_t)k * n + i) * n + sigma[k * n + i]] = 1.0;",
      "for (int i = 0; i < n; ++i) P[((size_t)k * n + sigma[k * n + i]) * n + i] = 1.0;", 0),
