@@ -1,0 +1,55 @@
+"""GPU parity on seeded random shapes and forms: stream counts 1-8, widths that take
+the MFMA path (multiples of 64) and widths that do not, token counts around the tile
+sizes, both stream types, the permutation, Sinkhorn-Knopp and subset forms.  Every
+token and every output is compared with the oracle; tolerances as in
+test_gpu_parity.py."""
+import math
+import random
+
+import pytest
+import torch
+
+import synth_inputs as si
+from gpu_harness import GpuLayer, desc_for, oracle_reference, rel_err, to_np64
+
+pytestmark = pytest.mark.gpu
+
+WIDTHS = [64, 128, 192, 256, 320, 512, 1024, 40, 72, 8, 96]
+TOKENS = [1, 7, 15, 16, 17, 63, 64, 65, 100, 127, 129, 200, 255, 257, 300, 511, 513, 700]
+
+
+def _draw(rng, case):
+    mode = rng.choice(["lite", "lite", "sk", "subset", "subset"])
+    io = rng.choice(["bf16", "bf16", "bf16", "f32"])
+    if mode == "subset":
+        n = rng.randint(1, 8)
+        K = rng.randint(1, min(128, math.factorial(n)))
+    else:
+        n, K = rng.randint(1, 5), 0
+    C, T = rng.choice(WIDTHS), rng.choice(TOKENS)
+    if n * C > 8192:
+        C = 64
+    iters = rng.choice([20, 20, 3, 1]) if mode == "sk" else 20
+    return si.Workload(name=f"random{case}", n=n, C=C, T=T, io=io, res_mode=mode, n_perm=K, sk_iters=iters)
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_random_shapes_against_the_oracle(seed):
+    rng = random.Random(seed)
+    failures = []
+    for case in range(40):
+        wl = _draw(rng, case)
+        print(f"case {wl}", flush=True)
+        inp = si.make_inputs(wl, seed=1000 * seed + case, device="cuda")
+        L = GpuLayer(desc_for(wl, perm=inp.get("perm")), inp)
+        L.forward_fused()
+        L.backward_fused()
+        torch.cuda.synchronize()
+        ref = oracle_reference(inp, wl)
+        out, coef, par = (1e-5, 1e-5, 1e-5) if wl.io == "f32" else (2e-2, 1e-4, 2e-3)
+        for name, tol in [("H_res", coef), ("H_pre", coef), ("H_post", coef), ("h", out), ("x_out", out),
+                          ("g_x", out), ("g_y", out), ("g_W", par), ("g_b", par), ("g_alpha", par)]:
+            e = rel_err(to_np64(getattr(L, name)), ref[name])
+            if not e <= tol:
+                failures.append(f"{wl.name} {wl}: {name} {e:.3e} > {tol}")
+    assert not failures, "\n".join(failures)
