@@ -1309,7 +1309,8 @@ __global__ __launch_bounds__(256, 2) void bwd_gw_kernel(
   const int64_t b0 = static_cast<int64_t>(blockIdx.y) * blks_per_chunk;
   int64_t b1 = b0 + blks_per_chunk;
   if (b1 > nblk) b1 = nblk;
-  if (b0 >= b1) return;
+  // (a chunk past the last token block still writes its zeros: the partial sums of every
+  // chunk are added afterwards)
 
   struct In {
     u32x4 X[CSW][2];
@@ -1356,16 +1357,18 @@ __global__ __launch_bounds__(256, 2) void bwd_gw_kernel(
       }
     }
   };
-  In cur, nxt;
-  load(cur, b0);
-  int64_t blk = b0;
-  for (; blk + 1 < b1; ++blk) {
-    load(nxt, blk + 1);
-    __builtin_amdgcn_sched_barrier(0);
+  if (b0 < b1) {
+    In cur, nxt;
+    load(cur, b0);
+    int64_t blk = b0;
+    for (; blk + 1 < b1; ++blk) {
+      load(nxt, blk + 1);
+      __builtin_amdgcn_sched_barrier(0);
+      process(cur);
+      cur = nxt;
+    }
     process(cur);
-    cur = nxt;
   }
-  process(cur);
 
   float *dst = out + static_cast<size_t>(blockIdx.y) * K * M;
 #pragma unroll

@@ -273,6 +273,11 @@ LONG_CASES = [
     _small("long_n4", n=4, C=64, T=40000 - 1),
     _small("long_n5", n=5, C=64, T=32768 + 130),
     si.Workload(name="long_n6_k24", n=6, C=128, T=32768 + 65, io="bf16", res_mode="subset", n_perm=24),
+    # wide backward with few logit tiles: 513 / 625 token blocks over 64 g_W chunks leave the
+    # last chunks without tokens (their partial sums must still be written, as zeros)
+    _small("long_n5_sk_empty_chunks", n=5, C=128, T=16385, res_mode="sk"),
+    si.Workload(name="long_n8_k9_empty_chunks", n=8, C=128, T=20000, io="bf16", res_mode="subset", n_perm=9),
+    si.Workload(name="long_n2_k2", n=2, C=256, T=50001, io="bf16", res_mode="subset", n_perm=2),
 ]
 
 
