@@ -97,19 +97,21 @@ __global__ __launch_bounds__(kBlock) void proj_generic_kernel(const void *__rest
 
   for (int m0 = 0; m0 < M; m0 += 32) {
     const int m = m0 + ml;
-    float acc[kTok];
+    // nC / 8 terms per thread (2048 at n C = 16384): carried in fp64 so that this path,
+    // the one f32 streams take, keeps its logits to fp32 rounding at any width
+    double acc[kTok];
 #pragma unroll
-    for (int i = 0; i < kTok; ++i) acc[i] = 0.f;
+    for (int i = 0; i < kTok; ++i) acc[i] = 0.0;
     if (m < M) {
       for (int k = ks; k < nC; k += 8) {
-        const float w = W[static_cast<size_t>(k) * M + m];
+        const double w = W[static_cast<size_t>(k) * M + m];
 #pragma unroll
-        for (int i = 0; i < kTok; ++i) acc[i] += IO::load1(x, row[i] + k) * w;
+        for (int i = 0; i < kTok; ++i) acc[i] += static_cast<double>(IO::load1(x, row[i] + k)) * w;
       }
     }
     __syncthreads();
 #pragma unroll
-    for (int i = 0; i < kTok; ++i) red[ks][i][ml] = acc[i];
+    for (int i = 0; i < kTok; ++i) red[ks][i][ml] = static_cast<float>(acc[i]);
     __syncthreads();
     if (threadIdx.x < kTok * 32) {
       const int i = threadIdx.x >> 5;

@@ -76,6 +76,8 @@ SMALL_CASES = [
     _small("f32_n3", n=3, C=40, T=19, io="f32"),
     _small("bf16_c4096", C=4096, T=70),                        # full width, several tiles + tail
     _small("one_token", C=64, T=1),
+    _small("f32_c4096", C=4096, T=300, io="f32"),              # f32 streams at full width: 1e-5 holds
+                                                               # (the plain projection sums in fp64)
     _small("sk_3iters", C=64, T=40, res_mode="sk", sk_iters=3),
 ]
 
