@@ -53,3 +53,35 @@ def test_random_shapes_against_the_oracle(seed):
             if not e <= tol:
                 failures.append(f"{wl.name} {wl}: {name} {e:.3e} > {tol}")
     assert not failures, "\n".join(failures)
+
+
+def test_random_shapes_with_many_tokens():
+    """The same with 16k to 65k tokens (narrow streams, so that the oracle still redoes
+    every token): token counts around the points where launch shapes change, and counts
+    that the token-chunk grids of the backward do not divide."""
+    rng = random.Random(0)
+    failures = []
+    for case in range(10):
+        mode = rng.choice(["lite", "sk", "subset"])
+        if mode == "subset":
+            n = rng.randint(2, 8)
+            K = rng.randint(1, min(96, math.factorial(n)))
+        else:
+            n, K = rng.randint(1, 5), 0
+        C = rng.choice([64, 128, 192, 256])
+        T = rng.choice([32639, 32640, 32641, 32768, 40000, 50001, 65539, 16383, 16385, 20000])
+        wl = si.Workload(name=f"many{case}", n=n, C=C, T=T, io="bf16", res_mode=mode, n_perm=K)
+        print(f"case {wl}", flush=True)
+        inp = si.make_inputs(wl, seed=77 + case, device="cuda")
+        L = GpuLayer(desc_for(wl, perm=inp.get("perm")), inp)
+        L.forward_fused()
+        L.backward_fused()
+        torch.cuda.synchronize()
+        ref = oracle_reference(inp, wl)
+        for name, tol in [("H_res", 1e-4), ("H_pre", 1e-4), ("H_post", 1e-4), ("h", 2e-2), ("x_out", 2e-2),
+                          ("g_x", 2e-2), ("g_y", 2e-2), ("g_W", 2e-3), ("g_b", 2e-3), ("g_alpha", 2e-3)]:
+            e = rel_err(to_np64(getattr(L, name)), ref[name])
+            if not e <= tol:
+                failures.append(f"{wl}: {name} {e:.3e} > {tol}")
+        del L, inp, ref
+    assert not failures, "\n".join(failures)
