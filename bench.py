@@ -46,7 +46,7 @@ def stage_bytes(stage: int, n: int, C: int, T: int, e: int) -> int:
 # kernel's readings; profiles/n4_c4096_bench_step.md), valid only for the kernel sources whose
 # digest is recorded with them: {workload: (csrc digest, {stage: bytes})}
 MEASURED_TRAFFIC = {
-    "n4_c4096": ("465d1f6374aebdc0", {
+    "n4_c4096": ("cd0cb42336ae1ba0", {
         1: int(1040.8 * 2**20 + 4.1 * 2**20),
         2: int(1028.0 * 2**20 + 256.0 * 2**20),
         3: int(1292.3 * 2**20 + 1024.0 * 2**20),
