@@ -20,11 +20,12 @@ OUTS = ("H_res", "H_pre", "H_post", "h", "x_out", "g_x", "g_y", "g_W", "g_b", "g
     si.Workload("graph_n5", n=5, C=128, T=300),
     si.Workload("graph_sk", n=4, C=256, T=257, res_mode="sk"),
     si.Workload("graph_f32", n=3, C=40, T=50, io="f32"),
+    si.Workload("graph_n8_k64", n=8, C=64, T=150, res_mode="subset", n_perm=64),
 ], ids=lambda w: w.name)
 def test_captured_step_replays_bitwise(wl):
     print(f"case {wl}", flush=True)
     inp = si.make_inputs(wl, seed=0, device="cuda")
-    L = GpuLayer(desc_for(wl), inp)
+    L = GpuLayer(desc_for(wl, perm=inp.get("perm")), inp)
     L.step()                                   # warm up outside the capture
     torch.cuda.synchronize()
     g = torch.cuda.CUDAGraph()
