@@ -85,3 +85,33 @@ def test_random_shapes_with_many_tokens():
                 failures.append(f"{wl}: {name} {e:.3e} > {tol}")
         del L, inp, ref
     assert not failures, "\n".join(failures)
+
+
+def test_random_shapes_with_16_byte_aligned_tensors():
+    """The C ABI asks for 16-byte alignment only: every stream tensor, inputs and outputs,
+    starts an odd multiple of 16 bytes past a 1 KiB boundary."""
+    from paper_2601_05732_amd.layer import empty_stream, place_stream
+    rng = random.Random(5)
+    failures = []
+    for case in range(30):
+        wl = _draw(rng, case)
+        print(f"case {wl}", flush=True)
+        inp = si.make_inputs(wl, seed=300 + case, device="cuda")
+        phase = lambda: 16 * rng.choice([1, 3, 5, 7, 9, 13, 21, 33, 47, 63])
+        for k in ("x", "y", "g_xout", "g_h"):
+            inp[k] = place_stream(inp[k], phase())
+        L = GpuLayer(desc_for(wl, perm=inp.get("perm")), inp)
+        for k in ("h", "x_out", "g_x", "g_y"):
+            t = getattr(L, k)
+            setattr(L, k, empty_stream(t.shape, t.dtype, t.device, phase()))
+        L.forward_fused()
+        L.backward_fused()
+        torch.cuda.synchronize()
+        ref = oracle_reference(inp, wl)
+        out, coef, par = (1e-5, 1e-5, 1e-5) if wl.io == "f32" else (2e-2, 1e-4, 2e-3)
+        for name, tol in [("H_res", coef), ("H_pre", coef), ("H_post", coef), ("h", out), ("x_out", out),
+                          ("g_x", out), ("g_y", out), ("g_W", par), ("g_b", par), ("g_alpha", par)]:
+            e = rel_err(to_np64(getattr(L, name)), ref[name])
+            if not e <= tol:
+                failures.append(f"{wl}: {name} {e:.3e} > {tol}")
+    assert not failures, "\n".join(failures)
