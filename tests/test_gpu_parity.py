@@ -323,3 +323,29 @@ def test_fused_backward_without_g_y(wl):
     for k, v in want.items():
         assert torch.equal(getattr(L, k), v), k
     assert bool((L.g_y.float() == 7.0).all())
+
+
+def test_two_streams_with_their_own_buffers_do_not_interfere():
+    """The library keeps no global state: the same calls issued on two streams (default
+    priority) with disjoint tensors and workspaces give the bits of sequential runs."""
+    wls = [_small("streams_a", C=512, T=3000), _small("streams_b", n=5, C=128, T=2000)]
+    layers, want = [], []
+    for k, wl in enumerate(wls):
+        inp = si.make_inputs(wl, seed=20 + k, device="cuda")
+        L = GpuLayer(desc_for(wl), inp)
+        L.step()
+        torch.cuda.synchronize()
+        want.append({nm: getattr(L, nm).clone() for nm in ("x_out", "g_x", "g_y", "g_W", "g_b", "g_alpha")})
+        for nm in want[-1]:
+            getattr(L, nm).zero_()
+        layers.append(L)
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    for rep in range(3):
+        for L, s in zip(layers, streams):
+            with torch.cuda.stream(s):
+                L.step()
+    torch.cuda.synchronize()
+    for L, w in zip(layers, want):
+        for nm, v in w.items():
+            assert torch.equal(getattr(L, nm), v), nm
