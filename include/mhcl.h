@@ -34,8 +34,10 @@
  *    hipStream_t passed as void*; NULL is the default stream).  Scratch memory
  *    comes from the caller as `ws` / `ws_bytes`, sized by
  *    mhcl_workspace_bytes(); its contents are undefined before and after a
- *    call.  There is no global mutable state: calls on different streams with
- *    disjoint outputs and workspaces may overlap.
+ *    call.  Calls on different streams with disjoint outputs and workspaces
+ *    may overlap.  The library keeps two pieces of state, each named where it
+ *    is used: the per-host-thread arming of mhcl_profile_next_call, and the
+ *    per-GPU static scratch array of mhcl_fwd_coeffs_pre_static.
  *  - Placement (performance only, never correctness): mhcl_bwd_fused runs
  *    about 5 % faster in its second pass when x, g_xout and g_x start at
  *    three different offsets modulo 1 KiB, in steps of 256 bytes (say 0, 256
@@ -143,10 +145,32 @@ int mhcl_pre(const mhcl_desc *desc, const void *x, const float *H_pre, void *h, 
 int mhcl_post(const mhcl_desc *desc, const void *x, const void *y, const float *H_res,
               const float *H_post, void *x_out, void *stream);
 
-/* mhcl_coeffs followed by mhcl_pre with fewer passes over x; same results. */
+/* mhcl_coeffs followed by mhcl_pre in one call (one validation, one workspace);
+ * same results, bit for bit.  x is read from HBM twice, once by the projection
+ * and once for h: h needs H_pre, which needs the whole row of the token. */
 int mhcl_fwd_coeffs_pre(const mhcl_desc *desc, const void *x, const float *W, const float *b,
                         const float *alpha, float *H_res, float *H_pre, float *H_post, void *h,
                         void *ws, size_t ws_bytes, void *stream);
+
+/* For callers that cannot allocate (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): mhcl_fwd_coeffs_pre without
+ * a workspace argument.  Its scratch is a static device array of
+ * MHCL_STATIC_SCRATCH_BYTES that every GPU the library runs on holds from the
+ * first use of the library on it until the process ends; the call allocates
+ * and frees nothing (no hipMalloc, no library allocator).  Same kernels, same
+ * results bit for bit.  Returns MHCL_ERR_WORKSPACE, and enqueues nothing, when
+ * mhcl_workspace_bytes(desc, MHCL_OP_FWD_COEFFS_PRE) exceeds the array (at
+ * n = 4, bf16 streams that is about T * 132 bytes + 2 MiB: the array covers
+ * n = 4, C = 4096 up to 100 000 tokens).  The first call on a GPU looks up the
+ * array's device address (hipGetSymbolAddress; make that call outside graph
+ * capture).  All calls on one GPU share the array: two such calls that overlap
+ * in time on one GPU (different streams or host threads) race; calls on one
+ * stream are ordered and safe.  The array's contents between calls are
+ * undefined; nothing in it has to be cleared. */
+#define MHCL_STATIC_SCRATCH_BYTES (16u << 20)
+int mhcl_fwd_coeffs_pre_static(const mhcl_desc *desc, const void *x, const float *W,
+                               const float *b, const float *alpha, float *H_res, float *H_pre,
+                               float *H_post, void *h, void *stream);
 
 /* ---- backward (chain rule on the definitions above) -------------------- */
 

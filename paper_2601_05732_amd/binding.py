@@ -25,7 +25,9 @@ _SYMBOLS = [
     "mhcl_perm_table", "mhcl_coeffs", "mhcl_pre", "mhcl_post", "mhcl_fwd_coeffs_pre",
     "mhcl_post_bwd", "mhcl_pre_bwd", "mhcl_coeffs_bwd", "mhcl_bwd_fused",
     "mhcl_logits", "mhcl_ds_chain", "mhcl_profile_next_call", "mhcl_debug_copy",
+    "mhcl_fwd_coeffs_pre_static",
 ]
+STATIC_SCRATCH_BYTES = 16 << 20   # MHCL_STATIC_SCRATCH_BYTES
 
 
 class MhclError(RuntimeError):
@@ -104,6 +106,7 @@ def lib():
         L.mhcl_pre.argtypes = [P] + [V] * 4
         L.mhcl_post.argtypes = [P] + [V] * 6
         L.mhcl_fwd_coeffs_pre.argtypes = [P] + [V] * 9 + [Z, V]
+        L.mhcl_fwd_coeffs_pre_static.argtypes = [P] + [V] * 9
         L.mhcl_post_bwd.argtypes = [P] + [V] * 10
         L.mhcl_pre_bwd.argtypes = [P] + [V] * 6
         L.mhcl_coeffs_bwd.argtypes = [P] + [V] * 12 + [Z, V]
@@ -206,6 +209,16 @@ def mhcl_fwd_coeffs_pre(d, x, W, b, alpha, H_res, H_pre, H_post, h, ws):
         _ptr(H_res, f, (d.T, d.n, d.n), "H_res"), _ptr(H_pre, f, (d.T, d.n), "H_pre"),
         _ptr(H_post, f, (d.T, d.n), "H_post"), _ptr(h, io, (d.T, d.C), "h"), wp, wb, _stream()),
         "mhcl_fwd_coeffs_pre")
+
+
+def mhcl_fwd_coeffs_pre_static(d, x, W, b, alpha, H_res, H_pre, H_post, h):
+    f, io = torch.float32, d.torch_dtype
+    _check(lib().mhcl_fwd_coeffs_pre_static(
+        ctypes.byref(d.c), _ptr(x, io, (d.T, d.n, d.C), "x"), _ptr(W, f, (d.n * d.C, d.M), "W"),
+        _ptr(b, f, (d.M,), "b"), _ptr(alpha, f, (3,), "alpha"),
+        _ptr(H_res, f, (d.T, d.n, d.n), "H_res"), _ptr(H_pre, f, (d.T, d.n), "H_pre"),
+        _ptr(H_post, f, (d.T, d.n), "H_post"), _ptr(h, io, (d.T, d.C), "h"), _stream()),
+        "mhcl_fwd_coeffs_pre_static")
 
 
 def mhcl_post_bwd(d, x, y, H_res, H_post, g_xout, g_x, g_y, g_H_res, g_H_post):

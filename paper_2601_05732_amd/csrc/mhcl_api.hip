@@ -2,6 +2,8 @@
 #include "mhcl_common.h"
 #include "mhcl_internal.h"
 
+#include <mutex>
+
 using namespace mhcl;
 
 namespace {
@@ -140,6 +142,55 @@ hipError_t run_coeffs_bwd_epilogue(const mhcl_desc &d, const float *u_raw, const
                                     g_H_post, o, s);
   return launch_coeffs_bwd_epilogue(d, proj_ksplit(d), u_raw, sumsq, b, alpha, g_H_res, g_H_pre,
                                     g_H_post, o, s);
+}
+
+// argument checks of mhcl_fwd_coeffs_pre and its allocation-free variant
+int check_fwd_coeffs_pre(const mhcl_desc *desc, const void *x, const float *W, const float *b,
+                         const float *alpha, const float *H_res, const float *H_pre,
+                         const float *H_post, const void *h) {
+  if (int e = check_desc(desc)) return e;
+  if (desc->T == 0) return MHCL_OK;   // per-token tensors may then be null
+  if (!all_ok(x, (const void *)W, (const void *)b, (const void *)alpha, (const void *)H_res,
+              (const void *)H_pre, (const void *)H_post, h))
+    return MHCL_ERR_INVALID_ARG;
+  return MHCL_OK;
+}
+
+// projection, coefficients, pre-aggregate with `ws` as the scratch (large enough, aligned)
+int run_fwd_coeffs_pre(const mhcl_desc &d, const void *x, const float *W, const float *b,
+                       const float *alpha, float *H_res, float *H_pre, float *H_post, void *h,
+                       void *ws, hipStream_t s) {
+  CoeffsWs w(d, ws);
+  Disarm disarm;
+  MHCL_HIP(run_projection(d, x, W, w.u_raw, w.sumsq, w.Wp, MHCL_STAGE_FWD_PROJ, s));
+  MHCL_HIP(run_coeffs_epilogue(d, w.u_raw, w.sumsq, b, alpha, H_res, H_pre, H_post, s));
+  {
+    StageBracket br(MHCL_STAGE_FWD_PRE, s);
+    MHCL_HIP(launch_pre(d, x, H_pre, h, s));
+  }
+  return MHCL_OK;
+}
+
+// Scratch of mhcl_fwd_coeffs_pre_static: one array per GPU, resident from the moment the
+// code object is loaded on that GPU until the process ends.  `scratch` itself is only a
+// host-side handle of the symbol; the array's device address is looked up once per device
+// and kernels are given that address.
+__device__ __align__(256) unsigned char scratch[MHCL_STATIC_SCRATCH_BYTES];
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices] = {};
+
+int static_scratch(void **out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return MHCL_ERR_HIP;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void *p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return MHCL_ERR_HIP;
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return MHCL_OK;
 }
 
 }  // namespace
@@ -290,23 +341,27 @@ int mhcl_post(const mhcl_desc *desc, const void *x, const void *y, const float *
 int mhcl_fwd_coeffs_pre(const mhcl_desc *desc, const void *x, const float *W, const float *b,
                         const float *alpha, float *H_res, float *H_pre, float *H_post, void *h,
                         void *ws, size_t ws_bytes, void *stream) {
-  if (int e = check_desc(desc)) return e;
+  if (int e = check_fwd_coeffs_pre(desc, x, W, b, alpha, H_res, H_pre, H_post, h)) return e;
   if (desc->T == 0) return MHCL_OK;   // per-token tensors may then be null
-  if (!all_ok(x, (const void *)W, (const void *)b, (const void *)alpha, (const void *)H_res,
-              (const void *)H_pre, (const void *)H_post, (const void *)h))
-    return MHCL_ERR_INVALID_ARG;
   if (!ws || !aligned16(ws) || ws_bytes < mhcl_workspace_bytes(desc, MHCL_OP_FWD_COEFFS_PRE))
     return MHCL_ERR_WORKSPACE;
-  hipStream_t s = static_cast<hipStream_t>(stream);
-  CoeffsWs w(*desc, ws);
-  Disarm disarm;
-  MHCL_HIP(run_projection(*desc, x, W, w.u_raw, w.sumsq, w.Wp, MHCL_STAGE_FWD_PROJ, s));
-  MHCL_HIP(run_coeffs_epilogue(*desc, w.u_raw, w.sumsq, b, alpha, H_res, H_pre, H_post, s));
-  {
-    StageBracket br(MHCL_STAGE_FWD_PRE, s);
-    MHCL_HIP(launch_pre(*desc, x, H_pre, h, s));
-  }
-  return MHCL_OK;
+  return run_fwd_coeffs_pre(*desc, x, W, b, alpha, H_res, H_pre, H_post, h, ws,
+                            static_cast<hipStream_t>(stream));
+}
+
+int mhcl_fwd_coeffs_pre_static(const mhcl_desc *desc, const void *x, const float *W,
+                               const float *b, const float *alpha, float *H_res, float *H_pre,
+                               float *H_post, void *h, void *stream) {
+  if (int e = check_fwd_coeffs_pre(desc, x, W, b, alpha, H_res, H_pre, H_post, h)) return e;
+  if (desc->T == 0) return MHCL_OK;
+  if (mhcl_workspace_bytes(desc, MHCL_OP_FWD_COEFFS_PRE) > MHCL_STATIC_SCRATCH_BYTES)
+    return MHCL_ERR_WORKSPACE;   // the shape needs more scratch than the static array holds
+  void *ws = nullptr;
+  if (int e = static_scratch(&ws)) return e;
+  // every word of the workspace this call reads is written by its own kernels first, so
+  // what the previous call left in the array does not matter
+  return run_fwd_coeffs_pre(*desc, x, W, b, alpha, H_res, H_pre, H_post, h, ws,
+                            static_cast<hipStream_t>(stream));
 }
 
 int mhcl_post_bwd(const mhcl_desc *desc, const void *x, const void *y, const float *H_res,
@@ -317,6 +372,7 @@ int mhcl_post_bwd(const mhcl_desc *desc, const void *x, const void *y, const flo
   if (!all_ok(x, y, (const void *)H_res, (const void *)H_post, g_xout, (const void *)g_x,
               (const void *)g_y, (const void *)g_H_res, (const void *)g_H_post))
     return MHCL_ERR_INVALID_ARG;
+  Disarm disarm;
   MHCL_HIP(launch_post_bwd(*desc, x, y, H_res, H_post, g_xout, g_x, g_y, g_H_res, g_H_post,
                            static_cast<hipStream_t>(stream)));
   return MHCL_OK;
@@ -328,6 +384,7 @@ int mhcl_pre_bwd(const mhcl_desc *desc, const void *x, const float *H_pre, const
   if (desc->T == 0) return MHCL_OK;   // per-token tensors may then be null
   if (!all_ok(x, (const void *)H_pre, g_h, (const void *)g_x, (const void *)g_H_pre))
     return MHCL_ERR_INVALID_ARG;
+  Disarm disarm;
   MHCL_HIP(launch_pre_bwd(*desc, x, H_pre, g_h, g_x, g_H_pre, static_cast<hipStream_t>(stream)));
   return MHCL_OK;
 }
