@@ -1,11 +1,10 @@
 """GPU parity: libmhcl (through its C ABI) against the fp64 oracle on the same
 seeded input bits.
 
-Tolerances (metric: max_e |got - ref| / max(|ref_e|, rms(ref)) per tensor):
+Tolerances (metric: max_e |got - ref| / max(|ref_e|, rms(ref)) per tensor), derived in
+gpu_harness.py:
   * f32 streams: 1e-5 on every output;
-  * bf16 streams: 2e-2 on bf16 outputs; fp32 coefficients 1e-4 (fp32
-    accumulation over nC terms); parameter gradients 2e-3 (their inputs, the
-    C-long dot products feeding g_z, are fp32 sums of bf16 products);
+  * bf16 streams: 2e-2 on bf16 outputs; fp32 coefficients 5e-5; parameter gradients 2e-4;
   * H_res rows and columns sum to 1 within 1e-6 (permutation form).
 """
 import numpy as np
@@ -13,14 +12,11 @@ import pytest
 import torch
 
 import synth_inputs as si
-from gpu_harness import GpuLayer, desc_for, oracle_reference, rel_err, to_np64
+from gpu_harness import (GpuLayer, desc_for, oracle_reference, rel_err, to_np64,
+                         TOL_F32, TOL_BF16_OUT, TOL_BF16_COEF, TOL_BF16_PARAM)
 
 pytestmark = pytest.mark.gpu
 
-TOL_F32 = 1e-5
-TOL_BF16_OUT = 2e-2
-TOL_BF16_COEF = 1e-4
-TOL_BF16_PARAM = 2e-3
 
 
 def _tols(wl):
@@ -103,11 +99,12 @@ def test_forward_and_backward_match_oracle(wl):
     fused_gx = to_np64(L.g_x)
     L.backward_separable()
     torch.cuda.synchronize()
-    # the separable chain rounds g_x to the stream type three times
+    # the separable chain (post_bwd, pre_bwd, coeffs_bwd) rounds g_x to the stream type three
+    # times; it still meets the bound of a bf16 output, and so do its g_y and its parameter
+    # gradients (other kernels than the fused call's)
+    _check_backward(L, ref, wl)
     t_out = _tols(wl)[0]
-    assert rel_err(to_np64(L.g_x), ref["g_x"]) <= (t_out if wl.io == "f32" else 2 * t_out)
     assert rel_err(to_np64(L.g_x), fused_gx) <= (t_out if wl.io == "f32" else 2 * t_out)
-    _check_backward(L, ref, wl) if wl.io == "f32" else None
     for name, tol in [("g_H_res", _tols(wl)[2]), ("g_H_pre", _tols(wl)[2]), ("g_H_post", _tols(wl)[2])]:
         assert rel_err(to_np64(getattr(L, name)), ref[name]) <= tol, name
 

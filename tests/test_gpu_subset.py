@@ -59,8 +59,7 @@ def test_subset_forward_and_backward_match_oracle(wl):
     torch.cuda.synchronize()
     t_out = _tols(wl)[0]
     assert rel_err(to_np64(L.g_x), fused_gx) <= (t_out if wl.io == "f32" else 2 * t_out)
-    if wl.io == "f32":
-        _check_backward(L, ref, wl)
+    _check_backward(L, ref, wl)      # the separable chain's g_x, g_y and parameter gradients
     if wl.n_perm == 1:
         sig = inp["perm"].cpu().numpy()[0]
         P = np.zeros((wl.n, wl.n)); P[np.arange(wl.n), sig] = 1
@@ -83,7 +82,7 @@ def test_all_permutations_in_order_reproduce_the_full_form():
     for k in ("H_pre", "H_post"):
         assert torch.equal(getattr(Lf, k), getattr(Ls, k)), k
     assert rel_err(to_np64(Ls.H_res), to_np64(Lf.H_res)) <= 1e-6       # other summation order
-    for k, tol in (("h", 0.0), ("x_out", 2e-2), ("g_x", 2e-2), ("g_y", 2e-2), ("g_W", 2e-3), ("g_b", 2e-3)):
+    for k, tol in (("h", 0.0), ("x_out", 2e-2), ("g_x", 2e-2), ("g_y", 2e-2), ("g_W", 2e-4), ("g_b", 2e-4)):
         assert rel_err(to_np64(getattr(Ls, k)), to_np64(getattr(Lf, k))) <= tol, k
 
 
