@@ -7,6 +7,8 @@ around the caller's layer function) and mhcl_bwd_fused.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--tokens T]
                     [--no-cpu-baseline] [--detail] [--graph] [--copy-calibration]
+    python bench.py --memsys        (runs the memory-system probe, a separate executable, and exits)
+    python bench.py --print-digest  (digest of the kernel sources, as recorded in profiles/)
 """
 from __future__ import annotations
 
@@ -42,18 +44,32 @@ def stage_bytes(stage: int, n: int, C: int, T: int, e: int) -> int:
     return per_token * T
 
 
-# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by the copy
-# kernel's readings; profiles/n4_c4096_bench_step.md), valid only for the kernel sources whose
-# digest is recorded with them: {workload: (csrc digest, {stage: bytes})}
-MEASURED_TRAFFIC = {
-    "n4_c4096": ("cd0cb42336ae1ba0", {
-        1: int(1040.8 * 2**20 + 4.1 * 2**20),
-        2: int(1028.0 * 2**20 + 256.0 * 2**20),
-        3: int(1292.3 * 2**20 + 1024.0 * 2**20),
-        4: int(2691.1 * 2**20 + 7.1 * 2**20),
-        5: int(2433.5 * 2**20 + 1296.2 * 2**20),
-    }),
-}
+# kernel that implements a stage (prefix of its name in the rocprofv3 tables under profiles/)
+STAGE_KERNEL = {1: "proj_mfma_kernel", 2: "pre_kernel", 3: "post_kernel", 4: "bwd_reduce_kernel",
+                5: "bwd_out_gw_kernel", 6: "bwd_gw"}
+
+
+def profile_traffic(workload: str):
+    """(digest, {kernel name: HBM bytes per launch}) from profiles/<workload>_bench_step.md: the
+    rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings, scaled by the copy kernel's, that the file
+    tabulates, and the digest of the kernel sources they were taken with."""
+    path = os.path.join(ROOT, "profiles", f"{workload}_bench_step.md")
+    digest, table = "", {}
+    try:
+        with open(path) as f:
+            for line in f:
+                if line.startswith("csrc digest:"):
+                    digest = line.split(":", 1)[1].strip()
+                cells = [c.strip() for c in line.strip().strip("|").split("|")]
+                if len(cells) == 5 and cells[0] and cells[0] != "kernel":
+                    try:
+                        table[cells[0]] = int((float(cells[3]) + float(cells[4])) * 2**20)
+                    except ValueError:
+                        pass
+    except OSError:
+        pass
+    return digest, table
+
 
 def csrc_digest() -> str:
     import hashlib
@@ -66,8 +82,15 @@ def csrc_digest() -> str:
 
 
 def measured_traffic(workload: str, stage: int):
-    digest, table = MEASURED_TRAFFIC.get(workload, ("", {}))
-    return table.get(stage) if digest == csrc_digest() else None
+    """HBM bytes per launch of the stage's kernel as tabulated under profiles/, or None when the
+    kernel sources have changed since (or nothing was recorded)."""
+    digest, table = profile_traffic(workload)
+    if not digest or digest != csrc_digest():
+        return None
+    for name, nbytes in table.items():
+        if name.startswith(STAGE_KERNEL.get(stage, "?")):
+            return nbytes
+    return None
 
 
 def _hip_runtime():
@@ -108,13 +131,19 @@ class HipEvents:
             self.rt.hipEventDestroy(h)
 
 
-def cpu_baseline(inp, wl, sample_tokens):
+def cpu_baseline(inp, wl, sample_tokens, threads=None):
     """The fp64 oracle, as it stands, on the first `sample_tokens` tokens of the
-    same workload (forward + backward), timed on the host cores."""
+    same workload (forward + backward), timed on the host cores (`threads`: None =
+    all the OpenMP runtime takes, else that many)."""
     import numpy as np
     import torch
 
     import oracle
+    cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    if threads is not None:
+        gomp = ctypes.CDLL("libgomp.so.1")      # the OpenMP runtime the oracle's library links
+        gomp.omp_set_num_threads(int(threads))
+        cores = int(threads)
     f64 = lambda t: t[:sample_tokens].detach().to("cpu", torch.float64).numpy()
     full = lambda t: t.detach().to("cpu", torch.float64).numpy()
     x, y = f64(inp["x"]), f64(inp["y"])
@@ -131,7 +160,6 @@ def cpu_baseline(inp, wl, sample_tokens):
     t0 = time.perf_counter()
     run(sample_tokens)
     dt = time.perf_counter() - t0
-    cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
     return {"value": sample_tokens / dt, "unit": "tokens/s", "cores": cores, "kind": "oracle",
             "sample": f"first {sample_tokens} of {wl.T} tokens, "
                       f"{'forward+backward' if wl.backward else 'forward'}, fp64, "
@@ -148,15 +176,30 @@ def main():
                     help="run the workload's shape with this many tokens instead of its own count "
                          "(a scaling aid; the headline figure is the default)")
     ap.add_argument("--cpu-sample", type=int, default=16384)
+    ap.add_argument("--cpu-sample-1thread", type=int, default=1024)
+    ap.add_argument("--memsys", action="store_true",
+                    help="run the memory-system probe (traffic skeletons of the path's access "
+                         "patterns; a separate executable) and exit")
+    ap.add_argument("--print-digest", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--detail", action="store_true", help="per-stage times on stderr")
     ap.add_argument("--graph", action="store_true",
                     help="capture one step in a HIP graph and time replays (for launch-bound small "
                          "shapes); the dominant kernel's time then comes from the eager warmup probe")
     ap.add_argument("--copy-calibration", action="store_true",
-                    help="also run the library's plain copy kernel on 1 GiB five times (a dispatch "
-                         "of known traffic, to scale hardware byte counters with)")
+                    help="accepted and ignored: the library's plain copy kernel now always runs on "
+                         "1 GiB five times before the warm-up (its rate is reported, and under "
+                         "rocprofv3 --pmc it is the dispatch of known traffic)")
     args = ap.parse_args()
+    if args.print_digest:
+        print(csrc_digest())
+        return
+    if args.memsys:
+        import subprocess
+        exe = os.path.join(ROOT, "paper_2601_05732_amd", "memsys_probe")
+        if not os.path.exists(exe):
+            sys.exit(f"{exe} is missing: build it with `python -m paper_2601_05732_amd.build`")
+        sys.exit(subprocess.run([exe]).returncode)    # nothing in this process has touched the GPU
     if args.gpus != 1:
         print("bench.py: this benchmark runs on one GPU only (tokens are independent, so the path "
               "shards over tokens; no multi-GPU figure is produced). Use --gpus 1.",
@@ -201,27 +244,26 @@ def main():
         mhcl.mhcl_bwd_fused(dd, i["x"], i["y"], i["W"], i["b"], i["alpha"], i["g_xout"], i["g_h"],
                             L.g_x, L.g_y, L.g_W, L.g_b, L.g_alpha, L.ws)
 
-    if args.copy_calibration:
-        lib.mhcl_debug_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t,
-                                        ctypes.c_void_p]
-        nbytes = 1 << 30
-        src = torch.empty(nbytes, dtype=torch.uint8, device="cuda:0").fill_(1)
-        dst = torch.empty_like(src)
-        cev = HipEvents(2)
-        rt = cev.rt
-        rt.hipEventRecord.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
-        stream = torch.cuda.current_stream().cuda_stream
-        for it in range(5):
-            if it == 1:
-                rt.hipEventRecord(cev.ev[0], stream)
-            lib.mhcl_debug_copy(dst.data_ptr(), src.data_ptr(), nbytes, stream)
-        rt.hipEventRecord(cev.ev[1], stream)
-        torch.cuda.synchronize()
-        ms = cev.elapsed_ms(0, 1) / 4
-        print(f"[copy] 1 GiB device copy: {ms:.3f} ms, {2 * nbytes / ms / 1e6:.1f} GB/s "
-              "(read + write)", file=sys.stderr)
-        cev.close()
-        del src, dst
+    # the library's plain copy kernel on 1 GiB: the yardstick beside the 8 TB/s peak (and, under
+    # rocprofv3 --pmc, a dispatch of known traffic to scale hardware byte counters with)
+    lib.mhcl_debug_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    nbytes = 1 << 30
+    src = torch.empty(nbytes, dtype=torch.uint8, device="cuda:0").fill_(1)
+    dst = torch.empty_like(src)
+    cev = HipEvents(2)
+    rt = cev.rt
+    rt.hipEventRecord.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
+    stream = torch.cuda.current_stream().cuda_stream
+    for it in range(5):
+        if it == 1:
+            rt.hipEventRecord(cev.ev[0], stream)
+        lib.mhcl_debug_copy(dst.data_ptr(), src.data_ptr(), nbytes, stream)
+    rt.hipEventRecord(cev.ev[1], stream)
+    torch.cuda.synchronize()
+    copy_gbs = 2 * nbytes / (cev.elapsed_ms(0, 1) / 4) / 1e6
+    print(f"[copy] 1 GiB device copy: {copy_gbs:.1f} GB/s (read + write)", file=sys.stderr)
+    cev.close()
+    del src, dst
 
     # warmup; the last warmup passes also find the stage that takes longest
     probe = HipEvents(2 * len(STAGES))
@@ -293,14 +335,17 @@ def main():
                                "forward (coeffs+pre, post)" + ("" if fwd_only else " + fused backward")
                                + (", HIP graph replay" if args.graph else ""),
                    "path_hbm_gbs_algorithmic": floor_bytes / (dt / args.steps) / 1e9,
-                   "path_frac_of_peak": floor_bytes / (dt / args.steps) / 1e9 / PEAK_HBM_GBS},
+                   "path_frac_of_peak": floor_bytes / (dt / args.steps) / 1e9 / PEAK_HBM_GBS,
+                   "copy_kernel_gbs": copy_gbs,
+                   "path_frac_of_copy": floor_bytes / (dt / args.steps) / 1e9 / copy_gbs},
         "roofline": {"bound": "hbm", "kernel": STAGES[dominant], "achieved": achieved,
                      "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": achieved / PEAK_HBM_GBS,
-                     "kernel_ms": kern_ms,
+                     "kernel_ms": kern_ms, "frac_of_copy": achieved / copy_gbs,
                      "traffic": measured_traffic(args.workload, dominant) if args.tokens <= 0 else None},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(inp, wl, min(args.cpu_sample, wl.T))
+        out["cpu_baseline_1thread"] = cpu_baseline(inp, wl, min(args.cpu_sample_1thread, wl.T), threads=1)
     print(json.dumps(out))
 
 

@@ -1,4 +1,5 @@
-"""Builds libmhcl.so (HIP, gfx950 only) next to this file with hipcc."""
+"""Builds libmhcl.so (HIP, gfx950 only) next to this file with hipcc, and the stand-alone
+memory-system probe (probe/memsys_probe.hip -> memsys_probe) that `bench.py --memsys` runs."""
 from __future__ import annotations
 
 import os
@@ -10,6 +11,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libmhcl.so")
 OBJ_DIR = os.path.join(_HERE, "_build")
+PROBE_SRC = os.path.join(_HERE, "probe", "memsys_probe.hip")
+PROBE = os.path.join(_HERE, "memsys_probe")
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
@@ -49,7 +52,19 @@ def build_library(verbose: bool = False) -> str:
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"link failed:\n{r.stderr}")
+    build_probe(verbose)
     return LIB
+
+
+def build_probe(verbose: bool = False) -> str:
+    """The traffic-skeleton executable (no part of the library; it links nothing of it)."""
+    cmd = [HIPCC, *[f for f in FLAGS if f != "-fPIC"], PROBE_SRC, "-o", PROBE]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"hipcc failed on {PROBE_SRC}:\n{r.stderr}")
+    return PROBE
 
 
 if __name__ == "__main__":
