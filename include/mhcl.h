@@ -207,8 +207,9 @@ int mhcl_coeffs_bwd(const mhcl_desc *desc, const void *x, const float *W, const 
  * For n >= 5 with bf16 streams and C a multiple of 64 (any form; with a
  * permutation subset only while n * ceil(M / 32) * 4 KiB of W plus the
  * per-token records fit the 160 KiB of LDS) the product W vr inside g_x uses
- * W rounded to fp16 (11 significant bits; the change is far below the bf16
- * rounding of g_x): entries of W must stay below 65504 in magnitude there. */
+ * W rounded to 11 significant bits (fp16 of W times a power of two chosen per
+ * call from max |W|, so any magnitude is fine); the change is far below the
+ * bf16 rounding of g_x. */
 int mhcl_bwd_fused(const mhcl_desc *desc, const void *x, const void *y, const float *W,
                    const float *b, const float *alpha, const void *g_xout, const void *g_h,
                    void *g_x, void *g_y, float *g_W, float *g_b, float *g_alpha,

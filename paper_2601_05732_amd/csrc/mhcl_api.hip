@@ -450,7 +450,7 @@ int mhcl_bwd_fused(const mhcl_desc *desc, const void *x, const void *y, const fl
   if (fast_bwd_ok(*desc)) {
     FastBwdWs f(*desc, ws);
     const bool wide = fast_bwd_wide(*desc);
-    MHCL_HIP(launch_pack_w_ab(*desc, M, W, f.Wp, f.Wa, s));
+    MHCL_HIP(launch_pack_w_ab(*desc, M, W, f, s));
     {
       StageBracket br(MHCL_STAGE_BWD_REDUCE, s);
       if (wide) {

@@ -259,8 +259,11 @@ __device__ __forceinline__ void pack_w_a_thread(int idx, const float *__restrict
 
 // W [K, M] fp32 -> A layout with ONE fp16 part per block (11 significant bits): for the
 // single-kernel wide pass 2, whose LDS holds one part only.  Block index (S*4 + h)*MS + ms.
+// Entries are multiplied by `scale`, a power of two chosen from max |W| so that the largest
+// entry lands in [2^13, 2^14): weights of any magnitude fit fp16, and the consumer multiplies
+// the MFMA result by 1 / scale (exact).
 __device__ __forceinline__ void pack_w_a16_thread(int idx, const float *__restrict__ W, int K, int M,
-                                                  int MS, uint4 *__restrict__ Wa) {
+                                                  int MS, float scale, uint4 *__restrict__ Wa) {
   const int lane = idx & 63, blk = idx >> 6;
   if (blk >= (K / 64) * 4 * MS) return;
   const int ms = blk % MS, h = (blk / MS) & 3, S = blk / (4 * MS);
@@ -270,7 +273,7 @@ __device__ __forceinline__ void pack_w_a16_thread(int idx, const float *__restri
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
     const int col = 32 * ms + 8 * q + e;
-    w[e] = col < M ? W[static_cast<size_t>(k) * M + col] : 0.f;
+    w[e] = col < M ? W[static_cast<size_t>(k) * M + col] * scale : 0.f;
   }
   uint4 v;
   v.x = cvt_pk_f16(w[0], w[1]); v.y = cvt_pk_f16(w[2], w[3]);
@@ -278,17 +281,61 @@ __device__ __forceinline__ void pack_w_a16_thread(int idx, const float *__restri
   Wa[static_cast<size_t>(blk) * 64 + lane] = v;
 }
 
+// max |W| in two stages without atomics: each of kWmaxBlocks blocks writes the maximum over
+// its grid-stride share of W; readers take the maximum of those.
+constexpr int kWmaxBlocks = 256;
+__global__ __launch_bounds__(256) void w_absmax_kernel(const float *__restrict__ W, size_t count,
+                                                       float *__restrict__ part) {
+  __shared__ float red[4];
+  float m = 0.f;
+  for (size_t i = static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x; i < count;
+       i += static_cast<size_t>(gridDim.x) * 256) {
+    const float a = fabsf(W[i]);
+    m = a > m ? a : m;      // (a NaN entry never wins: it poisons the products downstream anyway)
+  }
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = m;
+  __syncthreads();
+  if (threadIdx.x == 0) part[blockIdx.x] = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+}
+// the power of two that brings `wmax` into [2^13, 2^14) (1 for zero, infinite or NaN maxima)
+__device__ __forceinline__ float fp16_fit_scale(float wmax) {
+  if (!(wmax > 0.f) || !(wmax < 3.0e38f)) return 1.f;
+  int e;
+  (void)frexpf(wmax, &e);            // wmax = f * 2^e, f in [0.5, 1)
+  int k = 14 - e;                    // wmax * 2^k in [2^13, 2^14)
+  k = k > 126 ? 126 : (k < -126 ? -126 : k);
+  return ldexpf(1.f, k);
+}
+
 // Both layouts the backward needs in one launch: blocks [0, nb_b) write the B layout
-// (pass 1's projection), the rest the A layout (pass 2), with one fp16 part if `a16`.
+// (pass 1's projection), the rest the A layout (pass 2), with one fp16 part if `a16`;
+// then `wmax_part` holds kWmaxBlocks partial maxima of |W| and `wscale[0..1]` receives the
+// scale applied to the fp16 part and its inverse.
 __global__ __launch_bounds__(256) void pack_w_ab_kernel(const float *__restrict__ W, int K, int M,
                                                         int NT, int MS, int nb_b, int a16,
+                                                        const float *__restrict__ wmax_part,
+                                                        float *__restrict__ wscale,
                                                         uint4 *__restrict__ Wp,
                                                         uint4 *__restrict__ Wa) {
   const int b = blockIdx.x;
   if (b < nb_b) {
     pack_w_b_thread(b * 256 + threadIdx.x, W, K, M, NT, Wp);
   } else if (a16) {
-    pack_w_a16_thread((b - nb_b) * 256 + threadIdx.x, W, K, M, MS, Wa);
+    __shared__ float red[4];
+    static_assert(kWmaxBlocks == 256, "one partial maximum per thread");
+    float m = wmax_part[threadIdx.x];
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = m;
+    __syncthreads();
+    const float scale = fp16_fit_scale(fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3])));
+    if (b == nb_b && threadIdx.x == 0) {
+      wscale[0] = scale;
+      wscale[1] = 1.f / scale;
+    }
+    pack_w_a16_thread((b - nb_b) * 256 + threadIdx.x, W, K, M, MS, scale, Wa);
   } else {
     pack_w_a_thread((b - nb_b) * 256 + threadIdx.x, W, K, M, MS, Wa);
   }
@@ -982,10 +1029,10 @@ __global__ __launch_bounds__(256, 2) void wv_kernel(const u32x4 *__restrict__ Wa
 // as ONE 16-bit part (n = 5, 130 logits: 100 KiB per 64-column step; the bf16 pair would be 200):
 //   g_x[j] = sum_i H_res[i][j] g_xout[i] + H_pre[j] g_h + (W16 vr)[j] - x[j] coefx
 //   g_y    = sum_i H_post[i] g_xout[i]
-// W16 = fp16(W) (11 significant bits; |W| must stay below 65504, weights are O(1) or
-// less), and vr enters as fp16 hi + lo parts of vr / s with the token's own scale s
-// (F16ROWS of the per-token stage), so gradients of any magnitude fit; the MFMA
-// result is multiplied by s.  Rounding W to fp16 changes (W vr) by about 2^-12 of its
+// W16 = fp16(W * 2^k) (11 significant bits; the power of two is chosen per call from max |W|,
+// so weights of any magnitude fit), and vr enters as fp16 hi + lo parts of vr / s with the
+// token's own scale s (F16ROWS of the per-token stage), so gradients of any magnitude fit; the
+// MFMA result is multiplied by s / 2^k.  Rounding W to fp16 changes (W vr) by about 2^-12 of its
 // size, far below the rounding of g_x to bf16 that follows.  Nothing is written between
 // the passes (the two-kernel variant stores W vr as fp32 [T, nC] and reads it back).
 // One block of eight waves per CU, each wave 16 tokens per iteration; lane ownership
@@ -1008,7 +1055,8 @@ template <int N, int MS>
 __global__ __launch_bounds__(512, 1) void bwd_out_w16_kernel(
     const uint16_t *__restrict__ x, const uint16_t *__restrict__ g,
     const uint16_t *__restrict__ gh, const u32x4 *__restrict__ Wa, const float *__restrict__ cpk,
-    const uint16_t *__restrict__ vr_hi, const uint16_t *__restrict__ vr_lo, int MP32, int C,
+    const uint16_t *__restrict__ vr_hi, const uint16_t *__restrict__ vr_lo,
+    const float *__restrict__ wscale, int MP32, int C,
     int64_t T, int tokens_per_block, uint16_t *__restrict__ g_x, uint16_t *__restrict__ g_y) {
   using Cfg = OutW16Cfg<N, MS>;
   constexpr int NN = N * N, CP = Cfg::CP, CPS = Cfg::CPS, CP4 = CP / 4;
@@ -1027,6 +1075,7 @@ __global__ __launch_bounds__(512, 1) void bwd_out_w16_kernel(
   }
   __syncthreads();
   const u32x4 *wl = lds + lane;
+  const float inv_wscale = wscale[1];
   float *cps = reinterpret_cast<float *>(lds + N * kStreamVec) + wave * 16 * CPS;   // this wave's records
   const float *cpr = cps + r * CPS;                                                 // this lane's token
 
@@ -1084,7 +1133,8 @@ __global__ __launch_bounds__(512, 1) void bwd_out_w16_kernel(
       *reinterpret_cast<float4 *>(cps + tk * CPS + 4 * part) = rec[i];
     }
     __builtin_amdgcn_wave_barrier();
-    const float cx = cpr[NN + 2 * N], vscale = cpr[NN + 2 * N + 1];
+    // W16 holds W * wscale[0] and the vr rows hold vr / (the token's scale): undo both
+    const float cx = cpr[NN + 2 * N], vscale = cpr[NN + 2 * N + 1] * inv_wscale;
     float hq[N];
 #pragma unroll
     for (int i = 0; i < N; ++i) hq[i] = cpr[NN + N + i];
@@ -1718,6 +1768,8 @@ FastBwdWs::FastBwdWs(const mhcl_desc &d, void *ws) {
   vrT_lo = c.take<uint16_t>(Tpad * MP16);
   Wp = c.take<char>(packed_b_bytes(K, M));
   Wa = c.take<char>(packed_a_bytes(K, M));
+  wmax_part = c.take<float>(256);   // kWmaxBlocks
+  wscale = c.take<float>(2);
   {
     const int64_t tpb = out_gw_tokens_per_block(d);
     const size_t fused_chunks = static_cast<size_t>((d.T + tpb - 1) / tpb);
@@ -1729,14 +1781,22 @@ FastBwdWs::FastBwdWs(const mhcl_desc &d, void *ws) {
   bytes = c.off;
 }
 
-hipError_t launch_pack_w_ab(const mhcl_desc &d, int M, const float *W, void *Wp, void *Wa,
+hipError_t launch_pack_w_ab(const mhcl_desc &d, int M, const float *W, const FastBwdWs &w,
                             hipStream_t s) {
   const int K = d.n * d.C, NT = logit_tiles(M), MS = logit_steps(M);
   const int nb_b = ((K / 32) * NT * 64 + 255) / 256;
   const int nb_a = ((K / 64) * 4 * MS * 64 + 255) / 256;
-  // one fp16 part where the only reader is bwd_out_w16_kernel
+  // one fp16 part where the only reader is bwd_out_w16_kernel; its scale needs max |W| first
+  const bool a16 = fast_bwd_whi(d);
+  if (a16) {
+    hipLaunchKernelGGL(w_absmax_kernel, dim3(kWmaxBlocks), dim3(256), 0, s, W,
+                       static_cast<size_t>(K) * M, w.wmax_part);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
   hipLaunchKernelGGL(pack_w_ab_kernel, dim3(nb_b + nb_a), dim3(256), 0, s, W, K, M, NT, MS, nb_b,
-                     fast_bwd_whi(d) ? 1 : 0, static_cast<uint4 *>(Wp), static_cast<uint4 *>(Wa));
+                     a16 ? 1 : 0, w.wmax_part, w.wscale, reinterpret_cast<uint4 *>(w.Wp),
+                     reinterpret_cast<uint4 *>(w.Wa));
   return hipGetLastError();
 }
 
@@ -1889,7 +1949,7 @@ hipError_t launch_bwd_out_wide(const mhcl_desc &d, int M, const void *x, const v
         hipLaunchKernelGGL(kern, grid1, dim3(512), Cfg::kLdsBytes, s,
                            static_cast<const uint16_t *>(x), static_cast<const uint16_t *>(g_xout),
                            static_cast<const uint16_t *>(g_h), reinterpret_cast<const u32x4 *>(w.Wa),
-                           w.cpk, w.vr_hi, w.vr_lo, w.MP32, d.C, d.T, static_cast<int>(tpb1),
+                           w.cpk, w.vr_hi, w.vr_lo, w.wscale, w.MP32, d.C, d.T, static_cast<int>(tpb1),
                            static_cast<uint16_t *>(g_x), static_cast<uint16_t *>(g_y));
         return hipGetLastError();
       }

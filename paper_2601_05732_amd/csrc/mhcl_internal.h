@@ -119,14 +119,15 @@ bool fast_bwd_wide(const mhcl_desc &d);   // n >= 5 or a subset: pass 2 split in
 int gw_chunks_fast(const mhcl_desc &d);
 struct FastBwdWs {
   // gz: [ceil(T/64)][M+3] sums of g_z and g_z u over each 64 tokens
-  float *u_raw, *sumsq, *gH_res, *gH_pre, *gH_post, *cpk, *gz, *partials, *psum, *D;
+  // wmax_part: partial maxima of |W|; wscale: {scale, 1 / scale} of the fp16 copy of W
+  float *u_raw, *sumsq, *gH_res, *gH_pre, *gH_post, *cpk, *gz, *partials, *psum, *D, *wmax_part, *wscale;
   uint16_t *vr_hi, *vr_lo, *vrT_hi, *vrT_lo;
   char *Wp, *Wa;
   int CP, MP32, MP16, parts;
   size_t bytes;
   FastBwdWs(const mhcl_desc &d, void *ws);
 };
-hipError_t launch_pack_w_ab(const mhcl_desc &d, int M, const float *W, void *Wp, void *Wa,
+hipError_t launch_pack_w_ab(const mhcl_desc &d, int M, const float *W, const FastBwdWs &w,
                             hipStream_t s);
 hipError_t launch_bwd_reduce(const mhcl_desc &d, int M, const void *x, const void *y,
                              const void *g_xout, const void *g_h, const FastBwdWs &w,

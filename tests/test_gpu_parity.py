@@ -129,6 +129,25 @@ def test_paper_initialisation_case():
         assert rel_err(to_np64(getattr(L, name)), ref[name]) <= TOL_BF16_PARAM, name
 
 
+@pytest.mark.parametrize("n,C", [(5, 128), (4, 256)])
+def test_weights_of_large_magnitude(n, C):
+    # |W| up to a few 1e6 (with alpha small, so that the logits stay ordinary): the n = 5 backward
+    # carries W as ONE fp16 part, scaled by a power of two chosen from max |W|; without the
+    # scale every entry above 65504 would become infinite in g_x
+    s = 3.0e7
+    wl = _small(f"bigw_n{n}", n=n, C=C, T=150, alpha=(1 / s, 1 / s, 1 / s))
+    inp = si.make_inputs(wl, seed=5, device="cuda")
+    inp["W"] = inp["W"] * s
+    assert float(inp["W"].abs().max()) > 1e6
+    ref = oracle_reference(inp, wl)
+    L = GpuLayer(desc_for(wl), inp)
+    L.step()
+    torch.cuda.synchronize()
+    _check_forward(L, ref, wl)
+    _check_backward(L, ref, wl)
+    assert torch.isfinite(L.g_x.float()).all()
+
+
 def test_empty_input_is_a_no_op():
     wl = _small("empty", T=0)
     inp = si.make_inputs(wl, seed=0, device="cuda")
