@@ -39,23 +39,24 @@ from .layer import PHASE_G_X, PHASE_G_XOUT, PHASE_X, empty_stream
 
 class _Link:
     """What the post node leaves for the coefficient node of the same layer."""
-    __slots__ = ("y", "g_xout", "H_pre", "ws", "g_x_phase")
+    __slots__ = ("y", "g_xout", "H_pre", "ws", "g_x_phase", "perm")
 
-    def __init__(self, g_x_phase=PHASE_G_X):
+    def __init__(self, g_x_phase=PHASE_G_X, perm=None):
         self.y = self.g_xout = self.H_pre = self.ws = None
         self.g_x_phase = g_x_phase
+        self.perm = perm      # int8 [K, n] table of the permutation-subset form, else None
 
 
-def _desc(x, res_mode, sk_iters, eps):
+def _desc(x, res_mode, sk_iters, eps, perm=None):
     T, n, C = x.shape
     io = {torch.bfloat16: mhcl.BF16, torch.float32: mhcl.F32}[x.dtype]
-    return mhcl.Desc(n, C, T, io, res_mode, sk_iters, eps)
+    return mhcl.Desc(n, C, T, io, res_mode, sk_iters, eps, perm)
 
 
 class _CoeffsPre(torch.autograd.Function):
     @staticmethod
     def forward(ctx, x, W, b, alpha, link, res_mode, sk_iters, eps):
-        d = _desc(x, res_mode, sk_iters, eps)
+        d = _desc(x, res_mode, sk_iters, eps, link.perm)
         T, n, C = x.shape
         f = torch.float32
         H_res = torch.empty(T, n, n, device=x.device, dtype=f)
@@ -93,7 +94,7 @@ class _CoeffsPre(torch.autograd.Function):
 class _Post(torch.autograd.Function):
     @staticmethod
     def forward(ctx, x, y, H_res, H_post, link, res_mode, sk_iters, eps):
-        d = _desc(x, res_mode, sk_iters, eps)
+        d = _desc(x, res_mode, sk_iters, eps, link.perm)
         y = y.contiguous()
         x_out = empty_stream(x.shape, x.dtype, x.device, PHASE_X)
         mhcl.mhcl_post(d, x, y, H_res, H_post, x_out)
@@ -115,13 +116,15 @@ class _Post(torch.autograd.Function):
         return None, g_y, torch.zeros_like(H_res), torch.zeros_like(H_post), None, None, None, None
 
 
-def init_params(n: int, C: int, res_mode: int = mhcl.RES_LITE, one_index: int = 0, device="cuda"):
-    """W, b, alpha at the paper's initialisation (Sec. 4, "Initialization")."""
-    R = math.factorial(n) if res_mode == mhcl.RES_LITE else n * n
+def init_params(n: int, C: int, res_mode: int = mhcl.RES_LITE, one_index: int = 0, device="cuda",
+                n_perm: int = 0):
+    """W, b, alpha at the paper's initialisation (Sec. 4, "Initialization").  For a permutation
+    subset (``n_perm`` rows) the identity is expected as the table's first row."""
+    R = {mhcl.RES_LITE: math.factorial(n), mhcl.RES_SK: n * n, mhcl.RES_SUBSET: n_perm}[res_mode]
     b = torch.full((R + 2 * n,), -1.0, dtype=torch.float32)
     b[:R] = -8.0
-    if res_mode == mhcl.RES_LITE:
-        b[0] = 0.0                         # the identity is the first permutation in lexicographic order
+    if res_mode in (mhcl.RES_LITE, mhcl.RES_SUBSET):
+        b[0] = 0.0                         # the identity: first in lexicographic order / first row of the table
     else:
         b[:R:n + 1] = 0.0                  # the diagonal
     b[R + one_index] = 1.0
@@ -135,22 +138,32 @@ class HyperConnection(torch.nn.Module):
     """One layer: ``x_out = H_res x + H_post^T f(H_pre x)`` on ``x [T, n, C]``."""
 
     def __init__(self, n: int, C: int, res_mode: str = "lite", sk_iters: int = 20, eps: float = 1e-6,
-                 one_index: int = 0, device="cuda", layer_index: int = 0):
+                 one_index: int = 0, device="cuda", layer_index: int = 0, perm=None):
+        """res_mode: "lite" (all n! permutations), "sk" (Sinkhorn-Knopp) or "subset" (Sec. 5: only
+        the K permutations in ``perm``, an int8 tensor [K, n] with the identity as its first row,
+        n up to 8)."""
         super().__init__()
         self.n, self.C = n, C
+        if (res_mode == "subset") != (perm is not None):
+            raise ValueError("perm goes with res_mode 'subset', and only with it")
         # g_x of this layer is g_xout of the one below: alternate the two gradient phases
         # so that x, g_xout and g_x of a layer all differ (see layer.empty_stream)
         self.g_x_phase = PHASE_G_X if layer_index % 2 == 0 else PHASE_G_XOUT
-        self.res_mode = mhcl.RES_LITE if res_mode == "lite" else mhcl.RES_SK
+        self.res_mode = {"lite": mhcl.RES_LITE, "sk": mhcl.RES_SK, "subset": mhcl.RES_SUBSET}[res_mode]
         self.sk_iters, self.eps = sk_iters, eps
-        W, b, alpha = init_params(n, C, self.res_mode, one_index, device)
+        if perm is not None:
+            self.register_buffer("perm", perm.to(device=device, dtype=torch.int8).contiguous())
+        else:
+            self.perm = None
+        W, b, alpha = init_params(n, C, self.res_mode, one_index, device,
+                                  n_perm=0 if perm is None else int(perm.shape[0]))
         self.W, self.b, self.alpha = (torch.nn.Parameter(t) for t in (W, b, alpha))
 
     def forward(self, x: torch.Tensor, f):
         if x.dim() != 3 or x.shape[1] != self.n or x.shape[2] != self.C:
             raise ValueError(f"x must be [T, {self.n}, {self.C}], got {tuple(x.shape)}")
         x = x.contiguous()
-        link = _Link(self.g_x_phase)
+        link = _Link(self.g_x_phase, self.perm)
         cfg = (self.res_mode, self.sk_iters, self.eps)
         h, H_res, H_post, _ = _CoeffsPre.apply(x, self.W, self.b, self.alpha, link, *cfg)
         y = f(h)

@@ -12,23 +12,26 @@ The paper takes these statistics from trained models; those weights are not
 available, so each layer gets its own seeded Gaussian x, W, b and the spread
 of the residual logits is swept through alpha_res instead.
 
+The package draws no inputs itself: ``layer_stack`` takes them, or a callable
+that draws layer l's; the command line below uses the repository's seeded
+generator (``synth_inputs`` at the repository root).
+
 Run ``python -m paper_2601_05732_amd.diag`` for a table.
 """
 from __future__ import annotations
 
 import argparse
-import dataclasses
 
 import torch
 
-import synth_inputs as si
 from . import binding as mhcl
 from .layer import desc_for
 
 
-def layer_stack(wl: si.Workload, L: int, seed0: int = 0, device: str = "cuda", inputs=None):
-    """H [L,T,n,n], z [L,T,M], log_inv_nu [L,T] for L layers; layer l draws its
-    inputs with seed ``seed0 + l`` unless ``inputs`` (a list of L dicts) is given."""
+def layer_stack(wl, L: int, inputs, device: str = "cuda"):
+    """H [L,T,n,n], z [L,T,M], log_inv_nu [L,T] for L layers.  ``wl`` is a workload
+    record (fields n, C, T, M, io, res_mode, sk_iters, eps); ``inputs`` is a list of L
+    dicts with the GPU tensors x, W, b, alpha of each layer, or a callable ``l -> dict``."""
     d = desc_for(wl)
     f = torch.float32
     H = torch.empty(L, wl.T, wl.n, wl.n, device=device, dtype=f)
@@ -42,9 +45,8 @@ def layer_stack(wl: si.Workload, L: int, seed0: int = 0, device: str = "cuda", i
     Hp = torch.empty(wl.T, wl.n, device=device, dtype=f)
     Hq = torch.empty(wl.T, wl.n, device=device, dtype=f)
     ws = mhcl.new_workspace(d, mhcl.OP_COEFFS, device)
-    fwd_only = dataclasses.replace(wl, backward=False)
     for l in range(L):
-        inp = inputs[l] if inputs is not None else si.make_inputs(fwd_only, seed=seed0 + l, device=device)
+        inp = inputs(l) if callable(inputs) else inputs[l]
         mhcl.mhcl_coeffs(d, inp["x"], inp["W"], inp["b"], inp["alpha"], Hl, Hp, Hq, ws)
         mhcl.mhcl_logits(d, inp["x"], inp["W"], inp["b"], inp["alpha"], zl, sl, ws)
         H[l].copy_(Hl)
@@ -68,17 +70,17 @@ def _q(t: torch.Tensor, qs=(0.5, 0.99, 1.0)):
     return [float(torch.quantile(t, q)) if q < 1.0 else float(t.max()) for q in qs]
 
 
-def report(n=4, C=512, T=16384, layers=(6, 24), alphas=(1.0, 4.0, 8.0, 16.0), device="cuda"):
+def report(draw, layers=(6, 24), alphas=(1.0, 4.0, 8.0, 16.0), device="cuda"):
     """Prints, for each alpha_res and depth, quantiles of log(1/nu), of the
     per-matrix column-sum deviation and l1 error, and of the same for the
-    product over the layers, for Sinkhorn-Knopp (20) and the permutation form."""
+    product over the layers, for Sinkhorn-Knopp (20) and the permutation form.
+    ``draw(mode, alpha_res)`` returns (workload record, callable l -> inputs of layer l)."""
     rows = []
     for a in alphas:
         for mode in ("sk", "lite"):
-            wl = si.Workload(f"diag_{mode}", n=n, C=C, T=T, res_mode=mode, alpha=(a, 1.0, 1.0),
-                             backward=False)
+            wl, inputs = draw(mode, a)
             Lmax = max(layers)
-            H, _, spread = layer_stack(wl, Lmax, seed0=100, device=device)
+            H, _, spread = layer_stack(wl, Lmax, inputs, device=device)
             out = chain(H)
             for L in layers:
                 dev1 = (out["colsum"][:L] - 1).abs()
@@ -102,4 +104,14 @@ if __name__ == "__main__":
     ap.add_argument("--C", type=int, default=512)
     ap.add_argument("--T", type=int, default=16384)
     args = ap.parse_args()
-    report(n=args.n, C=args.C, T=args.T)
+    import os
+    import sys
+    sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+    import synth_inputs as si      # the repository's seeded input generator (command line only)
+
+    def _draw(mode, a):
+        wl = si.Workload(f"diag_{mode}", n=args.n, C=args.C, T=args.T, res_mode=mode,
+                         alpha=(a, 1.0, 1.0), backward=False)
+        return wl, (lambda l: si.make_inputs(wl, seed=100 + l, device="cuda"))
+
+    report(_draw)

@@ -90,7 +90,7 @@ def test_sk_worked_example_from_the_paper_on_the_gpu(golden_dir):
     inp["W"].zero_()
     inp["b"].zero_()
     inp["b"][: n * n] = torch.tensor(np.log(X0).reshape(-1), dtype=torch.float32)
-    H, z, spread = diag.layer_stack(wl, 24, inputs=[inp] * 24)
+    H, z, spread = diag.layer_stack(wl, 24, [inp] * 24)
     out = diag.chain(H)
     torch.cuda.synchronize()
     Hn = to_np64(H)
@@ -125,7 +125,7 @@ CHAIN_CASES = [
 @pytest.mark.parametrize("wl,L", CHAIN_CASES, ids=lambda v: v.name if isinstance(v, si.Workload) else str(v))
 def test_chain_matches_oracle(wl, L):
     print(f"case {wl} L={L}", flush=True)
-    H, _, _ = diag.layer_stack(wl, L, seed0=40)
+    H, _, _ = diag.layer_stack(wl, L, lambda l: si.make_inputs(wl, seed=40 + l, device="cuda"))
     out = diag.chain(H)
     torch.cuda.synchronize()
     ref = oracle.ds_chain(to_np64(H))
@@ -156,7 +156,7 @@ def test_depth_statistics_at_the_paper_shape():
     for mode in ("lite", "sk"):
         wl = si.Workload("depth_" + mode, n=4, C=512, T=T, res_mode=mode, alpha=(16.0, 1.0, 1.0),
                          backward=False)
-        H, _, spread = diag.layer_stack(wl, L, seed0=200)
+        H, _, spread = diag.layer_stack(wl, L, lambda l: si.make_inputs(wl, seed=200 + l, device="cuda"))
         out = diag.chain(H)
         torch.cuda.synchronize()
         pick = torch.tensor([0, 1, 63, 64, 127, 128, 4095, 8191, 8192, T - 65, T - 2, T - 1], device="cuda")
