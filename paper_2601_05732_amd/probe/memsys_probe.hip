@@ -206,6 +206,162 @@ __global__ __launch_bounds__(256) void pass2_flat(Bufs b, int wr) {
   }
 }
 
+
+// ---- (5) a single-read forward by exchange between blocks (upper bound of such a kernel).
+// Clusters of 32 blocks share 128-token groups; block p of a cluster owns 128 columns of every
+// stream (its piece, 128 KiB, stays in registers), publishes its partial sums (5 per token) as
+// tagged 64-bit words (relaxed agent-scope atomics; the tag is the iteration number, so no
+// fences are needed), reduces 4 of the group's tokens over the 32 parts, publishes their 4
+// coefficients, and produces h for its columns from the registers: x crosses the memory path
+// once.  Three pieces are in flight per block.  Every wait is bounded (kSpin polls, then the
+// block raises `err` and stops waiting); launched cooperatively so that all blocks are resident.
+typedef unsigned long long u64;
+constexpr int PARTS = 32, GT = 128;          // column parts per cluster, tokens per group
+constexpr int XNV = 5;                        // values exchanged per token in level 1 (sumsq + 4 pre logits)
+constexpr int RING = 8;
+constexpr int kSpin = 1 << 18;
+
+__device__ __forceinline__ void put(u64 *p, float v, unsigned tag) {
+  __hip_atomic_store(p, ((u64)tag << 32) | __float_as_uint(v), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ bool get(const u64 *p, unsigned tag, float &v, unsigned *err) {
+  v = 0.f;
+  if (*err) return false;     // once a wait has failed this lane waits for nothing any more
+  for (int i = 0; i < kSpin; ++i) {
+    const u64 w = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if ((unsigned)(w >> 32) == tag) { v = __uint_as_float((unsigned)w); return true; }
+    __builtin_amdgcn_s_sleep(2);
+  }
+  *err = 1;
+  v = 0.f;
+  return false;
+}
+
+// polls K words at p[0], p[stride], ... together until all carry `tag` (bounded)
+template <int K>
+__device__ __forceinline__ void get_many(const u64 *p, size_t stride, unsigned tag, float (&v)[K], unsigned *err) {
+#pragma unroll
+  for (int k = 0; k < K; ++k) v[k] = 0.f;
+  if (*err) return;
+  for (int i = 0; i < kSpin; ++i) {
+    u64 w[K];
+#pragma unroll
+    for (int k = 0; k < K; ++k) w[k] = __hip_atomic_load(p + k * stride, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    bool ok = true;
+#pragma unroll
+    for (int k = 0; k < K; ++k) ok = ok && (unsigned)(w[k] >> 32) == tag;
+    if (ok) {
+#pragma unroll
+      for (int k = 0; k < K; ++k) v[k] = __uint_as_float((unsigned)w[k]);
+      return;
+    }
+    __builtin_amdgcn_s_sleep(1);
+  }
+  *err = 1;
+}
+
+// l1: [RING][clusters][PARTS][GT][XNV] ; l2: [RING][clusters][GT][N]
+__global__ __launch_bounds__(512, 1) void xfwd(const u32x4 *__restrict__ x, u32x4 *__restrict__ h, long Tk,
+                                               u64 *__restrict__ l1, u64 *__restrict__ l2, unsigned *err,
+                                               int mode) {
+  extern __shared__ float lds[];   // [8 waves][16 tokens][XNV] partial exchange inside the block + padding for 1 block/CU
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, r = lane & 15, q = lane >> 4;
+  const int part = blockIdx.x % PARTS, cluster = blockIdx.x / PARTS, nclusters = gridDim.x / PARTS;
+  const long ngroups = Tk / GT;   // (T here is the kernel argument)
+  const int niter = (int)((ngroups - cluster + nclusters - 1) / nclusters);
+  // a wave's share of the piece: its 16 tokens, the block's 128 columns of every stream
+  u32x4 X0[N][4], X1[N][4], X2[N][4];   // ring of three pieces: [stream][16-byte vectors 4 s + q of the 128 columns]
+  const int cv = part * 16 + q;   // 16-byte vector index of column part*128 + 8 q
+  unsigned bad = 0;
+  auto step = [&](int it, u32x4 (&PA)[N][4], u32x4 (&PC)[N][4]) {
+    if (it >= niter + 2) return;
+    // ---- stage A: load piece `it`, partial sums, publish level 1
+    if (it < niter) {
+      const long g = cluster + (long)it * nclusters;
+      const long t = g * GT + wave * 16 + r;
+      auto &P = PA;
+#pragma unroll
+      for (int j = 0; j < N; ++j)
+#pragma unroll
+        for (int s = 0; s < 4; ++s) P[j][s] = x[(t * N + j) * RV + cv + s * 4];
+      // fake partial sums: XNV floats per token from the loaded words (lanes q = 0..3 of a token combined)
+      float v[XNV];
+#pragma unroll
+      for (int k = 0; k < XNV; ++k) v[k] = 0.f;
+#pragma unroll
+      for (int j = 0; j < N; ++j)
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+          v[0] += __uint_as_float((P[j][s].x & 0x007fffffu) | 0x3f800000u);
+          v[1 + j] += __uint_as_float((P[j][s].y & 0x007fffffu) | 0x3f800000u);
+        }
+#pragma unroll
+      for (int k = 0; k < XNV; ++k) { v[k] += __shfl_xor(v[k], 16, 64); v[k] += __shfl_xor(v[k], 32, 64); }
+      if (mode >= 1 && q == 0) {
+        u64 *dst = l1 + ((((size_t)(it % RING) * nclusters + cluster) * PARTS + part) * GT + wave * 16 + r) * XNV;
+#pragma unroll
+        for (int k = 0; k < XNV; ++k) put(dst + k, v[k], (unsigned)it + 1);
+      }
+    }
+    // ---- stage B: level 2 for group it-1: this block reduces tokens 4 part .. 4 part + 3 over the 32 parts
+    if (mode >= 1 && it >= 1 && it - 1 < niter) {
+      const int ib = it - 1;
+      if (wave == 0) {
+        // lane = (token pair tp = lane / 32, part p = lane % 32): polls its part's 2 x XNV words together,
+        // then the 32 parts are summed by a fixed shuffle tree
+        const int tp = lane >> 5, p = lane & 31;
+        const u64 *src = l1 + ((((size_t)(ib % RING) * nclusters + cluster) * PARTS + p) * GT + 4 * part + 2 * tp) * XNV;
+        float v[2 * XNV];
+        get_many<2 * XNV>(src, 1, (unsigned)ib + 1, v, &bad);
+#pragma unroll
+        for (int k = 0; k < 2 * XNV; ++k)
+#pragma unroll
+          for (int off = 1; off < 32; off <<= 1) v[k] += __shfl_xor(v[k], off, 64);
+        if (p < 2 * N) {      // lane p -> token 2 tp + p / N, coefficient p % N
+          const int tk = p / N, j = p % N;
+          float s0 = tk ? v[XNV] : v[0], u = 0.f;
+#pragma unroll
+          for (int k = 0; k < N; ++k) u = (j == k) ? (tk ? v[XNV + 1 + k] : v[1 + k]) : u;
+          const float hp = 1.f / (1.f + __expf(-(u / (s0 + 1.f))));
+          put(l2 + (((size_t)(ib % RING) * nclusters + cluster) * GT + 4 * part + 2 * tp + tk) * N + j, hp, (unsigned)ib + 1);
+        }
+      }
+    }
+    // ---- stage C: h for group it-2 from the registers
+    if (it >= 2) {
+      const int ic = it - 2;
+      const long g = cluster + (long)ic * nclusters;
+      const long t = g * GT + wave * 16 + r;
+      float hp[N];
+#pragma unroll
+      for (int j = 0; j < N; ++j) hp[j] = 1.f;
+      if (mode >= 1) {
+        const u64 *src = l2 + (((size_t)(ic % RING) * nclusters + cluster) * GT + wave * 16 + r) * N;
+        get_many<N>(src, 1, (unsigned)ic + 1, hp, &bad);
+      }
+      auto &P = PC;
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        u32x4 o = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int j = 0; j < N; ++j) {
+          const unsigned m = __float_as_uint(hp[j]);
+          o.x += P[j][s].x ^ m; o.y += P[j][s].y ^ m; o.z += P[j][s].z ^ m; o.w += P[j][s].w ^ m;
+        }
+        h[t * RV + cv + s * 4] = o;
+      }
+    }
+  };
+  for (int it = 0; it < niter + 2; it += 3) {
+    step(it, X0, X1);          // piece it -> X0; stage C of piece it - 2, which sits in X1
+    step(it + 1, X1, X2);
+    step(it + 2, X2, X0);
+  }
+  if (bad) err[0] = 1;
+  if (lds[(threadIdx.x + 1) & 255] == 123.456f) err[1] = 1;
+}
+
+
 int main() {
   const size_t xb = (size_t)T * N * C * 2, yb = (size_t)T * C * 2, slack = 4096;
   char *px, *pg, *py, *ph, *pgx, *pgy;
@@ -305,6 +461,40 @@ int main() {
         printf("chunks of %4ld tokens, pass 1 split in %2d column parts    : SEQ %.3f  MIX %.3f  PERS %.3f ms\n", Tc,
                parts, seq, mix, pers);
         fflush(stdout);
+      }
+    }
+  }
+  {
+    printf("\n## 3. single-read forward by exchange between blocks (5U: reads x once, writes h)\n");
+    int coop = 0;
+    CK(hipDeviceGetAttribute(&coop, hipDeviceAttributeCooperativeLaunch, 0));
+    if (!coop) {
+      printf("cooperative launch not supported: skipped\n");
+    } else {
+      const int ncl = 256 / PARTS;
+      const size_t l1n = (size_t)RING * ncl * PARTS * GT * XNV, l2n = (size_t)RING * ncl * GT * N;
+      u64 *l1, *l2;
+      unsigned *err;
+      CK(hipMalloc(&l1, l1n * 8)); CK(hipMalloc(&l2, l2n * 8)); CK(hipMalloc(&err, 64));
+      CK(hipMemset(err, 0, 64));
+      CK(hipFuncSetAttribute((const void *)xfwd, hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+      for (int mode : {0, 1}) {
+        float best = 1e9f;
+        for (int rep = 0; rep < 6; ++rep) {
+          CK(hipMemsetAsync(l1, 0, l1n * 8)); CK(hipMemsetAsync(l2, 0, l2n * 8));
+          CK(hipEventRecord(e0));
+          const u32x4 *xa = b.x; u32x4 *ha = b.gy; long Ta = T; u64 *a1 = l1, *a2 = l2; unsigned *ea = err; int m = mode;
+          void *args[] = {&xa, &ha, &Ta, &a1, &a2, &ea, &m};
+          CK(hipLaunchCooperativeKernel((const void *)xfwd, dim3(256), dim3(512), args, lds, 0));
+          CK(hipEventRecord(e1)); CK(hipEventSynchronize(e1));
+          float ms;
+          CK(hipEventElapsedTime(&ms, e0, e1));
+          if (rep > 0 && ms < best) best = ms;
+        }
+        unsigned herr[2];
+        CK(hipMemcpy(herr, err, 8, hipMemcpyDeviceToHost));
+        printf("%-56s: %.3f ms  %5.0f GB/s%s\n", mode ? "with the two-level exchange of partial sums" : "same loop without the exchange",
+               best, 5 * U / best / 1e6, herr[0] ? "  (a wait ran out)" : "");
       }
     }
   }
