@@ -284,15 +284,23 @@ __device__ __forceinline__ void pack_w_a16_thread(int idx, const float *__restri
 // max |W| in two stages without atomics: each of kWmaxBlocks blocks writes the maximum over
 // its grid-stride share of W; readers take the maximum of those.
 constexpr int kWmaxBlocks = 256;
-__global__ __launch_bounds__(256) void w_absmax_kernel(const float *__restrict__ W, size_t count,
+__global__ __launch_bounds__(256) void w_absmax_kernel(const float4 *__restrict__ W4, size_t count4,
                                                        float *__restrict__ part) {
+  // count4 16-byte vectors (K is a multiple of 64, so K * M is a multiple of 4); four loads in
+  // flight per lane
   __shared__ float red[4];
   float m = 0.f;
-  for (size_t i = static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x; i < count;
-       i += static_cast<size_t>(gridDim.x) * 256) {
-    const float a = fabsf(W[i]);
-    m = a > m ? a : m;      // (a NaN entry never wins: it poisons the products downstream anyway)
+  const size_t stride = static_cast<size_t>(gridDim.x) * 256;
+  size_t i = static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x;
+  auto take = [&](const float4 &v) {
+    // (a NaN entry never wins: it poisons the products downstream anyway)
+    m = fmaxf(m, fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
+  };
+  for (; i + 3 * stride < count4; i += 4 * stride) {
+    const float4 a = W4[i], b = W4[i + stride], c = W4[i + 2 * stride], d = W4[i + 3 * stride];
+    take(a); take(b); take(c); take(d);
   }
+  for (; i < count4; i += stride) take(W4[i]);
 #pragma unroll
   for (int off = 1; off < 64; off <<= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
   if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = m;
@@ -1789,8 +1797,9 @@ hipError_t launch_pack_w_ab(const mhcl_desc &d, int M, const float *W, const Fas
   // one fp16 part where the only reader is bwd_out_w16_kernel; its scale needs max |W| first
   const bool a16 = fast_bwd_whi(d);
   if (a16) {
-    hipLaunchKernelGGL(w_absmax_kernel, dim3(kWmaxBlocks), dim3(256), 0, s, W,
-                       static_cast<size_t>(K) * M, w.wmax_part);
+    hipLaunchKernelGGL(w_absmax_kernel, dim3(kWmaxBlocks), dim3(256), 0, s,
+                       reinterpret_cast<const float4 *>(W), static_cast<size_t>(K) * M / 4,
+                       w.wmax_part);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
