@@ -73,3 +73,35 @@ def test_static_scratch_rejects_shapes_beyond_the_array():
     rc = mhcl.lib().mhcl_fwd_coeffs_pre_static(ctypes.byref(d.c), p, p, p, p, p, p, p, p, None)
     assert rc == 3   # MHCL_ERR_WORKSPACE, nothing enqueued
     torch.cuda.synchronize()
+
+
+def test_static_scratch_call_under_graph_capture():
+    """The callers it is for: captured in a HIP graph (after one eager call, which looks up the
+    array's address), every replay gives the bits of the eager call, with new inputs and eager
+    work between the replays."""
+    wl = si.Workload("static_graph", n=4, C=512, T=1500, io="bf16")
+    inp = si.make_inputs(wl, seed=31, device="cuda:0")
+    d = desc_for(wl)
+    dev, f = inp["x"].device, torch.float32
+    T, n, C = d.T, d.n, d.C
+    outs = (torch.empty(T, n, n, device=dev, dtype=f), torch.empty(T, n, device=dev, dtype=f),
+            torch.empty(T, n, device=dev, dtype=f), torch.empty(T, C, device=dev, dtype=d.torch_dtype))
+    call = lambda: mhcl.mhcl_fwd_coeffs_pre_static(d, inp["x"], inp["W"], inp["b"], inp["alpha"], *outs)
+    call()
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        call()
+    for rep in range(3):
+        fresh = si.make_inputs(wl, seed=40 + rep, device="cuda:0")
+        for k in ("x", "W", "b"):
+            inp[k].copy_(fresh[k])
+        call()
+        torch.cuda.synchronize()
+        want = [t.clone() for t in outs]
+        for t in outs:
+            t.fill_(float("nan"))
+        g.replay()
+        torch.cuda.synchronize()
+        for name, a, b in zip(("H_res", "H_pre", "H_post", "h"), want, outs):
+            assert _same_bits(a, b), (rep, name)
