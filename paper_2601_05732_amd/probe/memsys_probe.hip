@@ -362,6 +362,119 @@ __global__ __launch_bounds__(512, 1) void xfwd(const u32x4 *__restrict__ x, u32x
 }
 
 
+
+// ---- (6) a single-pass backward where a whole 16-token tile of the backward inputs fits the
+// registers of one compute unit (n = 3, C = 1024, T = 65536: 16 x 16 KiB = 256 KiB): load the tile,
+// reduce per-token sums over the block through LDS, run a per-token stage on 16 lanes of one wave (a
+// chain of dependent instructions stands in for the coefficient arithmetic), produce the outputs
+// from the registers: 12U of traffic instead of the 19U of two passes.  W in both MFMA layouts (384
+// KiB at this shape) is re-read from L2 for every tile, and g_W needs a pass of its own over x (3U).
+namespace small {
+constexpr int N = 3, C = 1024, RV = C / 8;
+constexpr long T = 65536;
+constexpr int WVEC = 384 * 1024 / 16;    // 16-byte vectors of packed W (both layouts)
+
+template <int STAGE_FMAS, int WREAD>
+__global__ __launch_bounds__(512, 1) void single_pass(const u32x4 *__restrict__ x, const u32x4 *__restrict__ g,
+                                                      const u32x4 *__restrict__ y, const u32x4 *__restrict__ h,
+                                                      const u32x4 *__restrict__ W, u32x4 *__restrict__ gx,
+                                                      u32x4 *__restrict__ gy, long ntiles) {
+  __shared__ float part[8][16][8];
+  __shared__ float rec[16][8];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, r = lane & 15, q = lane >> 4;
+  const int cv = wave * 16 + q;     // the wave's 128 columns: vectors cv + 4 s, s = 0..3
+  for (long tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+    const long t = tile * 16 + r;
+    u32x4 X[N][4], G[N][4], Y[4], H[4];
+#pragma unroll
+    for (int j = 0; j < N; ++j)
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        X[j][s] = x[(t * N + j) * RV + cv + 4 * s];
+        G[j][s] = g[(t * N + j) * RV + cv + 4 * s];
+      }
+#pragma unroll
+    for (int s = 0; s < 4; ++s) { Y[s] = y[t * RV + cv + 4 * s]; H[s] = h[t * RV + cv + 4 * s]; }
+    // W of this wave's columns, both layouts: WVEC / 8 vectors per wave and tile, from L2
+    u32x4 wacc = {0u, 0u, 0u, 0u};
+    if (WREAD) {
+      const u32x4 *wp = W + wave * (WVEC / 8) + lane;
+#pragma unroll 8
+      for (int i = 0; i < WVEC / 8 / 64; ++i) wacc ^= wp[i * 64];
+    }
+    // partial sums of the wave's columns (8 floats per token), lanes q combined
+    float v[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) v[k] = 0.f;
+#pragma unroll
+    for (int j = 0; j < N; ++j)
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        v[j] += __uint_as_float((X[j][s].x & 0x007fffffu) | 0x3f800000u) * __uint_as_float((G[j][s].y & 0x007fffffu) | 0x3f800000u);
+        v[3 + j] += __uint_as_float((X[j][s].z & 0x007fffffu) | 0x3f800000u) * __uint_as_float((H[s].w & 0x007fffffu) | 0x3f800000u);
+      }
+    v[6] = __uint_as_float((Y[0].x & 0x007fffffu) | 0x3f800000u);
+    v[7] = __uint_as_float((wacc.x & 0x007fffffu) | 0x3f800000u);
+#pragma unroll
+    for (int k = 0; k < 8; ++k) { v[k] += __shfl_xor(v[k], 16, 64); v[k] += __shfl_xor(v[k], 32, 64); }
+    if (q == 0) {
+#pragma unroll
+      for (int k = 0; k < 8; ++k) part[wave][r][k] = v[k];
+    }
+    __syncthreads();
+    if (wave == 0 && lane < 16) {      // the per-token stage: one token per lane, a dependent chain
+      float s[8];
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        s[k] = 0.f;
+        for (int w = 0; w < 8; ++w) s[k] += part[w][lane][k];
+      }
+      float a = s[0] * 1e-3f;
+      for (int i = 0; i < STAGE_FMAS / 8; ++i) {      // STAGE_FMAS dependent instructions
+#pragma unroll
+        for (int k = 0; k < 8; ++k) a = __builtin_fmaf(a, 0.999f, s[k]);
+      }
+#pragma unroll
+      for (int k = 0; k < 8; ++k) rec[lane][k] = a + s[k] * 1e-3f;
+    }
+    __syncthreads();
+    float c[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) c[k] = rec[r][k];
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      const unsigned m0 = __float_as_uint(c[0]), m1 = __float_as_uint(c[1]);
+#pragma unroll
+      for (int j = 0; j < N; ++j) {
+        u32x4 o;
+        o.x = X[j][s].x ^ G[0][s].x ^ m0; o.y = X[j][s].y ^ G[1][s].y ^ m1; o.z = X[j][s].z ^ G[2][s].z ^ H[s].z; o.w = X[j][s].w ^ G[j][s].w ^ wacc.w;
+        gx[(t * N + j) * RV + cv + 4 * s] = o;
+      }
+      gy[t * RV + cv + 4 * s] = G[0][s] ^ G[1][s] ^ G[2][s];
+    }
+    __syncthreads();   // part / rec are rewritten by the next tile
+  }
+}
+
+// the separate g_W pass: reads x once (row order, 128-token blocks)
+__global__ __launch_bounds__(512, 1) void read_x(const u32x4 *__restrict__ x, unsigned *sink) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, r = lane & 15, q = lane >> 4;
+  const long t = (long)blockIdx.x * 128 + wave * 16 + r;
+  u32x4 acc = {0u, 0u, 0u, 0u};
+  for (int s = 0; s < C / 64; ++s) {
+    u32x4 X[N][2];
+#pragma unroll
+    for (int j = 0; j < N; ++j)
+#pragma unroll
+      for (int u = 0; u < 2; ++u) X[j][u] = x[(t * N + j) * RV + s * 8 + u * 4 + q];
+#pragma unroll
+    for (int j = 0; j < N; ++j) acc ^= X[j][0] ^ X[j][1];
+  }
+  if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x12345u) sink[0] = acc.y;
+}
+
+}  // namespace small
+
 int main() {
   const size_t xb = (size_t)T * N * C * 2, yb = (size_t)T * C * 2, slack = 4096;
   char *px, *pg, *py, *ph, *pgx, *pgy;
@@ -497,6 +610,29 @@ int main() {
                best, 5 * U / best / 1e6, herr[0] ? "  (a wait ran out)" : "");
       }
     }
+  }
+  {
+    using namespace small;
+    printf("\n## 4. single-pass backward with the 16-token tile in registers, n = 3, C = 1024, T = 65536 (12U + 3U)\n");
+    const size_t sxb = (size_t)small::T * small::N * small::C * 2, syb = (size_t)small::T * small::C * 2;
+    if (sxb > xb || syb > yb) { printf("buffers too small\n"); return 1; }
+    u32x4 *Wb;
+    CK(hipMalloc(&Wb, (size_t)WVEC * 16));
+    CK(hipMemset(Wb, 5, (size_t)WVEC * 16));
+    const long ntiles = small::T / 16;
+    const double SU = (double)small::T * small::C * 2;
+    const u32x4 *sx = (const u32x4 *)px, *sg = (const u32x4 *)pg, *sy = (const u32x4 *)py, *sh = (const u32x4 *)ph;
+    u32x4 *sgx = (u32x4 *)pgx, *sgy = (u32x4 *)pgy;
+    const float a = best_ms([&] { hipLaunchKernelGGL((single_pass<0, 0>), dim3(256), dim3(512), 0, 0, sx, sg, sy, sh, Wb, sgx, sgy, ntiles); });
+    const float b1 = best_ms([&] { hipLaunchKernelGGL((single_pass<1000, 0>), dim3(256), dim3(512), 0, 0, sx, sg, sy, sh, Wb, sgx, sgy, ntiles); });
+    const float c1 = best_ms([&] { hipLaunchKernelGGL((single_pass<1000, 1>), dim3(256), dim3(512), 0, 0, sx, sg, sy, sh, Wb, sgx, sgy, ntiles); });
+    const float d1 = best_ms([&] { hipLaunchKernelGGL((single_pass<3000, 1>), dim3(256), dim3(512), 0, 0, sx, sg, sy, sh, Wb, sgx, sgy, ntiles); });
+    const float rx = best_ms([&] { hipLaunchKernelGGL(read_x, dim3((unsigned)(small::T / 128)), dim3(512), 0, 0, sx, sink); });
+    printf("tile loop, bare (12U)                                   : %.3f ms  %5.0f GB/s\n", a, 12 * SU / a / 1e6);
+    printf("+ per-token stage of 1000 dependent instructions        : %.3f ms\n", b1);
+    printf("+ W (384 KiB) from L2 for every tile                    : %.3f ms\n", c1);
+    printf("the same with a stage of 3000 instructions              : %.3f ms\n", d1);
+    printf("separate pass over x for g_W (3U, reads only)           : %.3f ms\n", rx);
   }
   return 0;
 }
