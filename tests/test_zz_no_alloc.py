@@ -105,3 +105,16 @@ def test_static_scratch_call_under_graph_capture():
         torch.cuda.synchronize()
         for name, a, b in zip(("H_res", "H_pre", "H_post", "h"), want, outs):
             assert _same_bits(a, b), (rep, name)
+
+
+def test_static_scratch_empty_input_and_bad_arguments():
+    import ctypes
+    d0 = desc_for(si.Workload("static_empty", n=4, C=64, T=0, io="bf16"))
+    assert mhcl.lib().mhcl_fwd_coeffs_pre_static(ctypes.byref(d0.c), *([None] * 9)) == 0    # T = 0: nothing to do
+    d = desc_for(si.Workload("static_bad", n=4, C=64, T=8, io="bf16"))
+    t = torch.zeros(4096, device="cuda:0")
+    p = ctypes.c_void_p(t.data_ptr())
+    assert mhcl.lib().mhcl_fwd_coeffs_pre_static(ctypes.byref(d.c), None, p, p, p, p, p, p, p, None) == 1   # null x
+    odd = ctypes.c_void_p(t.data_ptr() + 4)
+    assert mhcl.lib().mhcl_fwd_coeffs_pre_static(ctypes.byref(d.c), odd, p, p, p, p, p, p, p, None) == 1    # misaligned
+    torch.cuda.synchronize()
