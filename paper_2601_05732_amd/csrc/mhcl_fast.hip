@@ -898,12 +898,14 @@ __global__ __launch_bounds__(256 * SLABS, SLABS == 1 ? 2 : 1) void bwd_out_gw_ke
       __builtin_amdgcn_sched_barrier(0);
     }
   };
-  // g_W rows of stream `wave` from the 64 tokens whose x tiles sit in LDS
-  auto gw_accumulate = [&](int64_t t0blk) {
-    const int64_t blk0 = t0blk >> 5;   // two 32-token blocks of vrT
+  // g_W rows of stream `wave` from the 64 tokens whose x tiles sit in LDS.  The vrT operands
+  // (two 32-token blocks: wave pairs (0,1) and (2,3)) are fetched by gw_fetch, which the main
+  // loop issues BEFORE the next iteration's x tiles: loads return in order, so requested after
+  // them these small L2 hits would wait for a whole HBM round trip.
+  auto gw_fetch = [&](int64_t t0blk, u32x4 (&va)[2][NT][2]) {
+    const int64_t blk0 = t0blk >> 5;
 #pragma unroll
-    for (int pr = 0; pr < 2; ++pr) {   // wave pairs (0,1) and (2,3) = one 32-token block each
-      u32x4 va[NT][2];
+    for (int pr = 0; pr < 2; ++pr) {
 #pragma unroll
       for (int mt = 0; mt < NT; ++mt) {
         const size_t row = (static_cast<size_t>(blk0 + pr) * MP16 + mt * 16 + r) * 32;
@@ -911,9 +913,14 @@ __global__ __launch_bounds__(256 * SLABS, SLABS == 1 ? 2 : 1) void bwd_out_gw_ke
         const u32x2 h1 = *reinterpret_cast<const u32x2 *>(vrT_hi + row + 16 + 4 * q);
         const u32x2 l0 = *reinterpret_cast<const u32x2 *>(vrT_lo + row + 4 * q);
         const u32x2 l1 = *reinterpret_cast<const u32x2 *>(vrT_lo + row + 16 + 4 * q);
-        va[mt][0] = u32x4{h0.x, h0.y, h1.x, h1.y};
-        va[mt][1] = u32x4{l0.x, l0.y, l1.x, l1.y};
+        va[pr][mt][0] = u32x4{h0.x, h0.y, h1.x, h1.y};
+        va[pr][mt][1] = u32x4{l0.x, l0.y, l1.x, l1.y};
       }
+    }
+  };
+  auto gw_accumulate = [&](const u32x4 (&va)[2][NT][2]) {
+#pragma unroll
+    for (int pr = 0; pr < 2; ++pr) {   // one 32-token block each
 #pragma unroll
       for (int u = 0; u < 2; ++u) {
         const u32x4 xa = xch[((wave * 4 + 2 * pr + 0) * 2 + u) * 64 + lane];
@@ -928,8 +935,8 @@ __global__ __launch_bounds__(256 * SLABS, SLABS == 1 ? 2 : 1) void bwd_out_gw_ke
           bt.z = cvt_pk_bf16(tb2[0], tb2[1]); bt.w = cvt_pk_bf16(tb2[2], tb2[3]);
 #pragma unroll
           for (int mt = 0; mt < NT; ++mt) {
-            acc[u][h][mt] = mfma16(va[mt][0], bt, acc[u][h][mt]);
-            acc[u][h][mt] = mfma16(va[mt][1], bt, acc[u][h][mt]);
+            acc[u][h][mt] = mfma16(va[pr][mt][0], bt, acc[u][h][mt]);
+            acc[u][h][mt] = mfma16(va[pr][mt][1], bt, acc[u][h][mt]);
           }
         }
       }
@@ -951,9 +958,12 @@ __global__ __launch_bounds__(256 * SLABS, SLABS == 1 ? 2 : 1) void bwd_out_gw_ke
 #pragma unroll
       for (int u = 0; u < 2; ++u) xch[((j * 4 + wave) * 2 + u) * 64 + lane] = in.X[j][u];
     __syncthreads();
+    u32x4 va[2][NT][2];
+    if (wave < N) gw_fetch(tb + static_cast<int64_t>(it) * 64, va);
+    __builtin_amdgcn_sched_barrier(0);
     load_x(in, t0 + 64);   // clamped to the block's last token when past the end
     __builtin_amdgcn_sched_barrier(0);
-    if (wave < N) gw_accumulate(tb + static_cast<int64_t>(it) * 64);
+    if (wave < N) gw_accumulate(va);
     __builtin_amdgcn_sched_barrier(0);
     process(in, t0);
   }
