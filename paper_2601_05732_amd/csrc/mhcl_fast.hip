@@ -405,7 +405,6 @@ __global__ __launch_bounds__(64 * WAVES, (WAVES == 4 || N <= 3) ? 2 : 1) void bw
   const int ncs = C / 64;   // 64-column steps; also per-stream stride of W in such steps
 
   struct Tile { u32x4 X[N][2], G[N][2], Y[2], H[2]; };
-  Tile tile;
   u32x4 wst[Cfg::WV];
   f32x4 acc[NT], ss = f32x4{0.f, 0.f, 0.f, 0.f};
   float dots[D];
@@ -414,7 +413,7 @@ __global__ __launch_bounds__(64 * WAVES, (WAVES == 4 || N <= 3) ? 2 : 1) void bw
 #pragma unroll
   for (int e = 0; e < D; ++e) dots[e] = 0.f;
 
-  auto load_tile = [&](int cs) {
+  auto load_tile = [&](Tile &tile, int cs) {
 #pragma unroll
     for (int j = 0; j < N; ++j)
 #pragma unroll
@@ -446,7 +445,7 @@ __global__ __launch_bounds__(64 * WAVES, (WAVES == 4 || N <= 3) ? 2 : 1) void bw
       lds[buf * Cfg::kStageVec + e] = wst[i];
     }
   };
-  auto compute = [&](int buf) {
+  auto compute = [&](const Tile &tile, int buf) {
     const u32x4 *wb = lds + buf * Cfg::kStageVec;
 #pragma unroll
     for (int j = 0; j < N; ++j) {
@@ -487,15 +486,41 @@ __global__ __launch_bounds__(64 * WAVES, (WAVES == 4 || N <= 3) ? 2 : 1) void bw
   load_w(turn(0));
   store_w(0);
   __syncthreads();
-  for (int cs = 0; cs < ncs; ++cs) {
-    const int nx = cs + 1 < ncs ? cs + 1 : cs;   // last step re-stages itself (unused)
-    load_w(turn(nx));
-    load_tile(turn(cs));
-    __builtin_amdgcn_sched_barrier(0);
-    store_w((cs + 1) & 1);
-    __builtin_amdgcn_sched_barrier(0);
-    compute(cs & 1);
-    __syncthreads();
+  if constexpr (WAVES == 8 && N >= 4) {
+    // One block per CU: nothing else keeps HBM busy while the block's waves, held in step by the
+    // barrier, compute.  So the NEXT step's tile is requested before this step's arithmetic
+    // (two tiles in registers); requests go out in the order W(next), tile(next), so that parking
+    // W in LDS waits for the W loads alone and computing on the current tile waits for nothing.
+    Tile ta, tb2;
+    load_tile(ta, turn(0));
+    auto step = [&](const Tile &cur, Tile &nxt, int cs) {
+      const int nx = cs + 1 < ncs ? cs + 1 : cs;   // the last step re-requests itself (unused)
+      load_w(turn(nx));
+      load_tile(nxt, turn(nx));
+      __builtin_amdgcn_sched_barrier(0);
+      store_w((cs + 1) & 1);
+      __builtin_amdgcn_sched_barrier(0);
+      compute(cur, cs & 1);
+      __syncthreads();
+    };
+    int cs = 0;
+    for (; cs + 1 < ncs; cs += 2) {
+      step(ta, tb2, cs);
+      step(tb2, ta, cs + 1);
+    }
+    if (cs < ncs) step(ta, tb2, cs);
+  } else {
+    Tile tile;
+    for (int cs = 0; cs < ncs; ++cs) {
+      const int nx = cs + 1 < ncs ? cs + 1 : cs;   // last step re-stages itself (unused)
+      load_w(turn(nx));
+      load_tile(tile, turn(cs));
+      __builtin_amdgcn_sched_barrier(0);
+      store_w((cs + 1) & 1);
+      __builtin_amdgcn_sched_barrier(0);
+      compute(tile, cs & 1);
+      __syncthreads();
+    }
   }
 
 #pragma unroll
