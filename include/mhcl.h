@@ -145,9 +145,18 @@ int mhcl_pre(const mhcl_desc *desc, const void *x, const float *H_pre, void *h, 
 int mhcl_post(const mhcl_desc *desc, const void *x, const void *y, const float *H_res,
               const float *H_post, void *x_out, void *stream);
 
-/* mhcl_coeffs followed by mhcl_pre in one call (one validation, one workspace);
- * same results, bit for bit.  x is read from HBM twice, once by the projection
- * and once for h: h needs H_pre, which needs the whole row of the token. */
+/* mhcl_coeffs and mhcl_pre in one call (one validation, one workspace).
+ * bf16 streams with at most 32 logits, C in {1024, 2048, 4096} and at least
+ * 512 * 65536 / C tokens: ONE kernel reads x from HBM once and produces the
+ * projection, H_pre and h from the same register tile (groups of 16 tokens
+ * shared by C / 256 thread blocks that exchange their partial sums; needs the
+ * 256 compute units of the device free for its 256 blocks, see the source).
+ * The projection's sum over n C terms is then split differently from
+ * mhcl_coeffs, so H_* agree with it to fp32 rounding of the logits and h to
+ * one bf16 step.  Every other shape, or a device that cannot hold the 256
+ * blocks at once: mhcl_coeffs followed by mhcl_pre, bit for bit (x is then
+ * read twice: h needs H_pre, which needs the token's whole row).
+ * Results are reproducible bit for bit from call to call either way. */
 int mhcl_fwd_coeffs_pre(const mhcl_desc *desc, const void *x, const float *W, const float *b,
                         const float *alpha, float *H_res, float *H_pre, float *H_post, void *h,
                         void *ws, size_t ws_bytes, void *stream);
@@ -157,9 +166,11 @@ int mhcl_fwd_coeffs_pre(const mhcl_desc *desc, const void *x, const float *W, co
  * a workspace argument.  Its scratch is a static device array of
  * MHCL_STATIC_SCRATCH_BYTES that every GPU the library runs on holds from the
  * first use of the library on it until the process ends; the call allocates
- * and frees nothing (no hipMalloc, no library allocator).  Same kernels, same
- * results bit for bit.  Returns MHCL_ERR_WORKSPACE, and enqueues nothing, when
- * mhcl_workspace_bytes(desc, MHCL_OP_FWD_COEFFS_PRE) exceeds the array (at
+ * and frees nothing (no hipMalloc, no library allocator).  It always runs the
+ * kernels of mhcl_coeffs followed by mhcl_pre, with their results bit for bit
+ * (the single-read kernel needs more scratch than the array at the shapes where
+ * it pays).  Returns MHCL_ERR_WORKSPACE, and enqueues nothing, when
+ * mhcl_workspace_bytes(desc, MHCL_OP_COEFFS) exceeds the array (at
  * n = 4, bf16 streams that is about T * 132 bytes + 2 MiB: the array covers
  * n = 4, C = 4096 up to 100 000 tokens).  The first call on a GPU looks up the
  * array's device address (hipGetSymbolAddress; make that call outside graph

@@ -126,12 +126,12 @@ hipError_t run_projection(const mhcl_desc &d, const void *x, const float *W, flo
 
 // per-token coefficients from the projection: compile-time tables for the full
 // permutation and Sinkhorn-Knopp forms, the run-time table for a subset
-hipError_t run_coeffs_epilogue(const mhcl_desc &d, const float *u_raw, const float *sumsq,
-                               const float *b, const float *alpha, float *H_res, float *H_pre,
-                               float *H_post, hipStream_t s) {
+hipError_t run_coeffs_epilogue(const mhcl_desc &d, int parts, const float *u_raw,
+                               const float *sumsq, const float *b, const float *alpha,
+                               float *H_res, float *H_pre, float *H_post, hipStream_t s) {
   if (coeffs_group_ok(d))
-    return launch_coeffs_group(d, proj_ksplit(d), u_raw, sumsq, b, alpha, H_res, H_pre, H_post, s);
-  return launch_coeffs_epilogue(d, proj_ksplit(d), u_raw, sumsq, b, alpha, H_res, H_pre, H_post, s);
+    return launch_coeffs_group(d, parts, u_raw, sumsq, b, alpha, H_res, H_pre, H_post, s);
+  return launch_coeffs_epilogue(d, parts, u_raw, sumsq, b, alpha, H_res, H_pre, H_post, s);
 }
 hipError_t run_coeffs_bwd_epilogue(const mhcl_desc &d, const float *u_raw, const float *sumsq,
                                    const float *b, const float *alpha, const float *g_H_res,
@@ -156,14 +156,37 @@ int check_fwd_coeffs_pre(const mhcl_desc *desc, const void *x, const float *W, c
   return MHCL_OK;
 }
 
-// projection, coefficients, pre-aggregate with `ws` as the scratch (large enough, aligned)
+// scratch of mhcl_fwd_coeffs_pre: the larger of the two layouts where the single-read kernel applies
+size_t fwd_coeffs_pre_ws_bytes(const mhcl_desc &d) {
+  const size_t two = CoeffsWs(d, nullptr).bytes;
+  if (!fwd_once_ok(d)) return two;
+  const size_t one = OnceWs(d, nullptr).bytes;
+  return one > two ? one : two;
+}
+
+// projection, coefficients, pre-aggregate with `ws` as the scratch (aligned; large enough for
+// the single-read layout if `once`, else for the two-kernel layout)
 int run_fwd_coeffs_pre(const mhcl_desc &d, const void *x, const float *W, const float *b,
                        const float *alpha, float *H_res, float *H_pre, float *H_post, void *h,
-                       void *ws, hipStream_t s) {
-  CoeffsWs w(d, ws);
+                       void *ws, bool once, hipStream_t s) {
   Disarm disarm;
+  if (once && fwd_once_ok(d)) {
+    OnceWs w(d, ws);
+    MHCL_HIP(launch_pack_w_b(d, logits(d), W, w.Wp, s));
+    bool ran = false;
+    {
+      StageBracket br(MHCL_STAGE_FWD_PROJ, s);
+      MHCL_HIP(launch_fwd_once(d, logits(d), x, b, alpha, w, h, s, &ran));
+    }
+    if (ran) {
+      MHCL_HIP(run_coeffs_epilogue(d, w.parts, w.u_part, w.sumsq_part, b, alpha, H_res, H_pre,
+                                   H_post, s));
+      return MHCL_OK;
+    }
+  }
+  CoeffsWs w(d, ws);
   MHCL_HIP(run_projection(d, x, W, w.u_raw, w.sumsq, w.Wp, MHCL_STAGE_FWD_PROJ, s));
-  MHCL_HIP(run_coeffs_epilogue(d, w.u_raw, w.sumsq, b, alpha, H_res, H_pre, H_post, s));
+  MHCL_HIP(run_coeffs_epilogue(d, proj_ksplit(d), w.u_raw, w.sumsq, b, alpha, H_res, H_pre, H_post, s));
   {
     StageBracket br(MHCL_STAGE_FWD_PRE, s);
     MHCL_HIP(launch_pre(d, x, H_pre, h, s));
@@ -219,8 +242,8 @@ size_t mhcl_workspace_bytes(const mhcl_desc *desc, int op) {
   if (check_desc(desc) != MHCL_OK) return 0;
   size_t b = 0;
   switch (op) {
-    case MHCL_OP_COEFFS:
-    case MHCL_OP_FWD_COEFFS_PRE: b = CoeffsWs(*desc, nullptr).bytes; break;
+    case MHCL_OP_COEFFS: b = CoeffsWs(*desc, nullptr).bytes; break;
+    case MHCL_OP_FWD_COEFFS_PRE: b = fwd_coeffs_pre_ws_bytes(*desc); break;
     case MHCL_OP_COEFFS_BWD: b = BwdWs(*desc, nullptr, false).bytes; break;
     case MHCL_OP_BWD_FUSED:
       b = fast_bwd_ok(*desc) ? FastBwdWs(*desc, nullptr).bytes : BwdWs(*desc, nullptr, true).bytes;
@@ -277,7 +300,8 @@ int mhcl_coeffs(const mhcl_desc *desc, const void *x, const float *W, const floa
   CoeffsWs w(*desc, ws);
   Disarm disarm;
   MHCL_HIP(run_projection(*desc, x, W, w.u_raw, w.sumsq, w.Wp, MHCL_STAGE_FWD_PROJ, s));
-  MHCL_HIP(run_coeffs_epilogue(*desc, w.u_raw, w.sumsq, b, alpha, H_res, H_pre, H_post, s));
+  MHCL_HIP(run_coeffs_epilogue(*desc, proj_ksplit(*desc), w.u_raw, w.sumsq, b, alpha, H_res, H_pre,
+                               H_post, s));
   return MHCL_OK;
 }
 
@@ -345,7 +369,7 @@ int mhcl_fwd_coeffs_pre(const mhcl_desc *desc, const void *x, const float *W, co
   if (desc->T == 0) return MHCL_OK;   // per-token tensors may then be null
   if (!ws || !aligned16(ws) || ws_bytes < mhcl_workspace_bytes(desc, MHCL_OP_FWD_COEFFS_PRE))
     return MHCL_ERR_WORKSPACE;
-  return run_fwd_coeffs_pre(*desc, x, W, b, alpha, H_res, H_pre, H_post, h, ws,
+  return run_fwd_coeffs_pre(*desc, x, W, b, alpha, H_res, H_pre, H_post, h, ws, true,
                             static_cast<hipStream_t>(stream));
 }
 
@@ -354,13 +378,13 @@ int mhcl_fwd_coeffs_pre_static(const mhcl_desc *desc, const void *x, const float
                                float *H_post, void *h, void *stream) {
   if (int e = check_fwd_coeffs_pre(desc, x, W, b, alpha, H_res, H_pre, H_post, h)) return e;
   if (desc->T == 0) return MHCL_OK;
-  if (mhcl_workspace_bytes(desc, MHCL_OP_FWD_COEFFS_PRE) > MHCL_STATIC_SCRATCH_BYTES)
+  if (CoeffsWs(*desc, nullptr).bytes > MHCL_STATIC_SCRATCH_BYTES)
     return MHCL_ERR_WORKSPACE;   // the shape needs more scratch than the static array holds
   void *ws = nullptr;
   if (int e = static_scratch(&ws)) return e;
   // every word of the workspace this call reads is written by its own kernels first, so
   // what the previous call left in the array does not matter
-  return run_fwd_coeffs_pre(*desc, x, W, b, alpha, H_res, H_pre, H_post, h, ws,
+  return run_fwd_coeffs_pre(*desc, x, W, b, alpha, H_res, H_pre, H_post, h, ws, false,
                             static_cast<hipStream_t>(stream));
 }
 

@@ -112,6 +112,22 @@ hipError_t launch_pack_w_b(const mhcl_desc &d, int M, const float *W, void *Wp, 
 hipError_t launch_proj_mfma(const mhcl_desc &d, int M, const void *x, const void *Wp, float *u_raw,
                             float *sumsq, hipStream_t s);
 
+// Single-read forward (projection slices, H_pre and h from one read of x): bf16 fast path
+// with at most 32 logits, C in {1024, 2048, 4096}, enough tokens to fill the pipeline.
+bool fwd_once_ok(const mhcl_desc &d);
+struct OnceWs {
+  float *u_part, *sumsq_part;   // [parts][T][M], [parts][T]: one slice per 256-column part
+  char *Wp;                     // packed W (B layout)
+  unsigned long long *xchg;     // exchange rings of the kernel (zeroed by its launcher)
+  size_t xchg_words, bytes;
+  int parts;
+  OnceWs(const mhcl_desc &d, void *ws);
+};
+// *ran == false on return with hipSuccess: this device cannot hold the kernel's grid at
+// once; nothing was launched and the caller takes the two-kernel path.  w.Wp must hold W.
+hipError_t launch_fwd_once(const mhcl_desc &d, int M, const void *x, const float *b,
+                           const float *alpha, const OnceWs &w, void *h, hipStream_t s, bool *ran);
+
 // fused backward on the fast path (needs fast_bwd_ok(desc))
 bool fast_bwd_ok(const mhcl_desc &d);
 bool fast_bwd_whi(const mhcl_desc &d);    // wide case, n >= 5, where W fits LDS as one fp16 part: that pass 2 as one kernel

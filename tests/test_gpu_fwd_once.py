@@ -1,0 +1,95 @@
+"""The single-read forward behind mhcl_fwd_coeffs_pre (Sec. 3.2 Eqs. (4)-(5), Sec. 2 Eq. (1)): at
+shapes where it applies the call must run that kernel (no pre-aggregate stage of its own), match
+the oracle on every token, agree with the separable calls, and repeat bit for bit on a reused
+workspace (its exchange rings start from zero in every call)."""
+import ctypes
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2601_05732_amd as mhcl
+import synth_inputs as si
+from bench import HipEvents
+from gpu_harness import (GpuLayer, TOL_BF16_COEF, TOL_BF16_OUT, desc_for, oracle_reference, rel_err,
+                         to_np64)
+
+pytestmark = pytest.mark.gpu
+
+STAGE_FWD_PRE = 2
+
+# (the smallest token counts at which the kernel is used: 32 groups of 16 tokens per cluster,
+#  256 / (C / 256) clusters; ragged tails on purpose)
+CASES = [
+    si.Workload("once_n4_c4096", n=4, C=4096, T=8192 + 7, io="bf16", backward=False),
+    si.Workload("once_n4_c2048_sk", n=4, C=2048, T=16384, io="bf16", res_mode="sk", backward=False),
+    si.Workload("once_n3_c1024", n=3, C=1024, T=32768 + 33, io="bf16", backward=False),
+    si.Workload("once_n2_c1024", n=2, C=1024, T=32768 + 1, io="bf16", backward=False),
+    si.Workload("once_n4_c2048_k12", n=4, C=2048, T=16384 + 17, io="bf16", res_mode="subset", n_perm=12,
+                backward=False),
+]
+
+
+def _pre_stage_recorded(L):
+    """True if the next mhcl_fwd_coeffs_pre runs a pre-aggregate kernel of its own."""
+    lib = mhcl.lib()
+    lib.mhcl_profile_next_call.argtypes = [ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
+    ev = HipEvents(2)
+    assert lib.mhcl_profile_next_call(STAGE_FWD_PRE, ev.ev[0], ev.ev[1]) == 0
+    L.forward_fused()
+    torch.cuda.synchronize()
+    try:
+        ev.elapsed_ms(0, 1)
+        return True
+    except RuntimeError:
+        return False
+    finally:
+        ev.close()
+
+
+@pytest.mark.parametrize("wl", CASES, ids=lambda w: w.name)
+def test_single_read_forward_matches_oracle_and_separable_calls(wl):
+    inp = si.make_inputs(wl, seed=3, device="cuda")
+    d = desc_for(wl, perm=inp.get("perm"))
+    assert mhcl.workspace_bytes(d, mhcl.OP_FWD_COEFFS_PRE) > mhcl.workspace_bytes(d, mhcl.OP_COEFFS), \
+        "the shape is meant to take the single-read kernel (it needs one slice per 256 columns)"
+    L = GpuLayer(d, inp)
+    L.ws.fill_(0xA5)     # whatever a workspace holds must not matter
+    assert not _pre_stage_recorded(L), "mhcl_fwd_coeffs_pre ran the two-kernel path"
+    got = {k: getattr(L, k).clone() for k in ("H_res", "H_pre", "H_post", "h", "x_out")}
+    # every token against the oracle
+    ref = oracle_reference(inp, wl, backward=False)
+    for k in ("H_res", "H_pre", "H_post"):
+        err = rel_err(to_np64(got[k]), ref[k].reshape(got[k].shape))
+        assert err <= TOL_BF16_COEF, (k, err)
+    for k in ("h", "x_out"):
+        err = rel_err(to_np64(got[k]), ref[k].reshape(got[k].shape))
+        assert err <= TOL_BF16_OUT, (k, err)
+    if wl.res_mode != "sk":   # (20 Sinkhorn-Knopp iterations only approach these sums)
+        rs = to_np64(got["H_res"]).sum(-1)
+        cs = to_np64(got["H_res"]).sum(-2)
+        assert np.abs(rs - 1).max() <= 1e-6 and np.abs(cs - 1).max() <= 1e-6
+    # a second call on the same workspace: the same bits
+    L.forward_fused()
+    torch.cuda.synchronize()
+    for k, v in got.items():
+        assert torch.equal(getattr(L, k), v), f"{k} differs between two calls"
+    # the separable calls split the projection's fp32 sum over n C terms differently: the
+    # coefficients agree to a few fp32 roundings of the logits, h to one bf16 step
+    L.forward_separable()
+    torch.cuda.synchronize()
+    for k in ("H_res", "H_pre", "H_post"):
+        err = rel_err(to_np64(getattr(L, k)), to_np64(got[k]))
+        assert err <= 2e-5, (k, err)
+    dh = (L.h.float() - got["h"].float()).abs()
+    err = float((dh / got["h"].float().abs().clamp_min(1e-3)).max())
+    assert err <= 2 ** -7, err
+
+
+def test_shapes_outside_keep_the_two_kernel_path():
+    for wl in (si.Workload("small_t", n=4, C=4096, T=8192 - 16, io="bf16"),
+               si.Workload("odd_c", n=4, C=4096 + 64, T=8192, io="bf16"),
+               si.Workload("n5", n=5, C=1024, T=16384, io="bf16")):
+        inp = si.make_inputs(wl, seed=0, device="cuda")
+        L = GpuLayer(desc_for(wl), inp)
+        assert _pre_stage_recorded(L), wl.name

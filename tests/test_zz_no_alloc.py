@@ -1,6 +1,7 @@
 """The allocation-free forward entry point (mhcl_fwd_coeffs_pre_static, scratch in a static
-device array) against mhcl_fwd_coeffs_pre with a caller workspace: same kernels, so every
-output must agree bit for bit; two calls in a row, the second on a smaller input, so that
+device array) against mhcl_fwd_coeffs_pre with a caller workspace: at these shapes both run the
+same kernels (the projection, the coefficient stage, the pre-aggregate), so every output must
+agree bit for bit; two calls in a row, the second on a smaller input, so that
 what the first left in the shared array is shown not to leak into the second.  Also against
 the oracle, at the tolerances of the parity tests.
 """
