@@ -172,13 +172,14 @@ int run_fwd_coeffs_pre(const mhcl_desc &d, const void *x, const float *W, const 
   Disarm disarm;
   if (once && fwd_once_ok(d)) {
     OnceWs w(d, ws);
-    MHCL_HIP(launch_pack_w_b(d, logits(d), W, w.Wp, s));
-    bool ran = false;
-    {
-      StageBracket br(MHCL_STAGE_FWD_PROJ, s);
-      MHCL_HIP(launch_fwd_once(d, logits(d), x, b, alpha, w, h, s, &ran));
-    }
-    if (ran) {
+    bool usable = false;
+    MHCL_HIP(prepare_fwd_once(d, logits(d), w, s, &usable));
+    if (usable) {
+      MHCL_HIP(launch_pack_w_b(d, logits(d), W, w.Wp, s));
+      {
+        StageBracket br(MHCL_STAGE_FWD_PROJ, s);
+        MHCL_HIP(launch_fwd_once(d, logits(d), x, b, alpha, w, h, s));
+      }
       MHCL_HIP(run_coeffs_epilogue(d, w.parts, w.u_part, w.sumsq_part, b, alpha, H_res, H_pre,
                                    H_post, s));
       return MHCL_OK;

@@ -123,10 +123,13 @@ struct OnceWs {
   int parts;
   OnceWs(const mhcl_desc &d, void *ws);
 };
-// *ran == false on return with hipSuccess: this device cannot hold the kernel's grid at
-// once; nothing was launched and the caller takes the two-kernel path.  w.Wp must hold W.
+// Before the kernel: *usable == false on return with hipSuccess means that this device
+// cannot hold the kernel's grid at once (the caller then takes the two-kernel path);
+// otherwise the exchange rings have been zeroed on `s`.
+hipError_t prepare_fwd_once(const mhcl_desc &d, int M, const OnceWs &w, hipStream_t s, bool *usable);
+// the kernel itself; w.Wp must hold the packed W
 hipError_t launch_fwd_once(const mhcl_desc &d, int M, const void *x, const float *b,
-                           const float *alpha, const OnceWs &w, void *h, hipStream_t s, bool *ran);
+                           const float *alpha, const OnceWs &w, void *h, hipStream_t s);
 
 // fused backward on the fast path (needs fast_bwd_ok(desc))
 bool fast_bwd_ok(const mhcl_desc &d);

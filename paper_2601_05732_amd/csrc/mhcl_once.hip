@@ -9,20 +9,22 @@
 //      of W (resident in LDS for the block's whole life) and writes the partial logits and
 //      the partial sum of squares as slice `part` of u_raw / sumsq (the coefficient stage
 //      adds the slices in order, as it does for a K split),
-//   B  two groups later, reduces the partial pre-logits and sums of squares of ITS share of
-//      the group's tokens over all parts, in part order, and publishes H_pre of those tokens,
-//   C  another two groups later, reads H_pre of all 16 tokens and writes its 256 columns of h
-//      from the piece it still holds.
+//      publishes its partial pre-logits and sum of squares to the cluster,
+//   B  three groups later, adds those of ITS share of the group's tokens (16 / parts of them)
+//      over all parts, in part order, and publishes H_pre of those tokens,
+//   C  another three groups later, reads H_pre of all 16 tokens and writes its 256 columns of
+//      h from the piece it still holds (eight pieces in registers, 16 registers each at n = 4).
 // The blocks of a cluster exchange those few values through memory as 64-bit words that carry
 // a tag (the group's number + 1) next to the value, written and read with relaxed agent-scope
 // atomics: a word is either the old one or the complete new one, so no fence is needed and
 // nothing is ever read before it is valid.  Exchange rings are zeroed before the launch.
-// All blocks must be resident at once: one block per compute unit, 256 blocks.
+// The blocks of a cluster must be resident together: 256 blocks, one per compute unit.
 // Every wait is bounded: a lane that does not see its tag after kOnceSpin polls gives up for
 // good and its results become NaN, so a lost block shows up in the outputs instead of hanging.
 #include "mhcl_common.h"
 #include "mhcl_internal.h"
 #include "mhcl_mfma.h"
+#include <atomic>
 
 namespace mhcl {
 
@@ -42,6 +44,7 @@ constexpr int kOncePF = 1, kOnceDB = 3, kOnceDC = 6;
 constexpr int kOnceXR = 8;
 constexpr int kOnceSpin = 1 << 20;
 constexpr int kOnceBlocks = 256;
+constexpr int kOnceMaxDevices = 64;
 
 template <int N, int NT>
 struct OnceCfg {
@@ -308,18 +311,25 @@ hipError_t dispatch_once(int n, int NT, F &&f) {
   return hipErrorInvalidValue;
 }
 
-// once per process: 256 blocks of this kernel fit the device at once
-bool device_takes_once(const void *kern, int lds) {
+// Whether the current device holds 256 blocks of the kernel at once; asked once per device
+// and kernel (the answer is cached: 0 unknown, 1 yes, 2 no).
+bool device_takes_once(const void *kern, int lds, std::atomic<int> (&cache)[kOnceMaxDevices]) {
   int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess) return false;
-  int cus = 0, per_cu = 0;
-  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
-    return false;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kOnceMaxDevices) return false;
+  // (every time: the attribute belongs to the function on the current device)
   if (hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
     return false;
-  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, 512, lds) != hipSuccess)
-    return false;
-  return static_cast<int64_t>(per_cu) * cus >= kOnceBlocks;
+  int known = cache[dev].load(std::memory_order_relaxed);
+  if (known == 0) {
+    int cus = 0, per_cu = 0;
+    const bool ok =
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess &&
+        hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, 512, lds) == hipSuccess &&
+        static_cast<int64_t>(per_cu) * cus >= kOnceBlocks;
+    known = ok ? 1 : 2;
+    cache[dev].store(known, std::memory_order_relaxed);
+  }
+  return known == 1;
 }
 
 }  // namespace
@@ -348,19 +358,26 @@ OnceWs::OnceWs(const mhcl_desc &d, void *ws) {
   bytes = c.off;
 }
 
+hipError_t prepare_fwd_once(const mhcl_desc &d, int M, const OnceWs &w, hipStream_t s, bool *usable) {
+  *usable = false;
+  return dispatch_once(d.n, logit_tiles(M), [&](auto nn, auto nt) {
+    constexpr int N = decltype(nn)::value, NT = decltype(nt)::value;
+    const void *kern = reinterpret_cast<const void *>(fwd_once_kernel<N, NT>);
+    static std::atomic<int> cache[kOnceMaxDevices];   // zero-initialised
+    if (!device_takes_once(kern, OnceCfg<N, NT>::kLdsBytes, cache)) return hipSuccess;
+    *usable = true;
+    // exchange rings start from zero: tags count from 1 in every launch
+    return launch_fill_zero(reinterpret_cast<float *>(w.xchg), w.xchg_words * 2, s);
+  });
+}
+
 hipError_t launch_fwd_once(const mhcl_desc &d, int M, const void *x, const float *b,
-                           const float *alpha, const OnceWs &w, void *h, hipStream_t s, bool *ran) {
-  *ran = false;
+                           const float *alpha, const OnceWs &w, void *h, hipStream_t s) {
   const int parts = w.parts, nclusters = kOnceBlocks / parts;
   return dispatch_once(d.n, logit_tiles(M), [&](auto nn, auto nt) {
     constexpr int N = decltype(nn)::value, NT = decltype(nt)::value;
     const void *kern = reinterpret_cast<const void *>(fwd_once_kernel<N, NT>);
     constexpr int lds = OnceCfg<N, NT>::kLdsBytes;
-    static const bool usable = device_takes_once(kern, lds);
-    if (!usable) return hipSuccess;   // the caller takes the two-kernel path
-    // exchange rings start from zero: tags count from 1 in every launch
-    hipError_t e = launch_fill_zero(reinterpret_cast<float *>(w.xchg), w.xchg_words * 2, s);
-    if (e != hipSuccess) return e;
     const uint16_t *xa = static_cast<const uint16_t *>(x);
     const u32x4 *wp = reinterpret_cast<const u32x4 *>(w.Wp);
     int C = d.C, Ma = M, R = res_logits(d), pa = parts;
@@ -373,12 +390,13 @@ hipError_t launch_fwd_once(const mhcl_desc &d, int M, const void *x, const float
     const float *ba = b, *aa = alpha;
     void *args[] = {&xa, &wp, &C, &Ma, &R, &T, &ba, &aa, &eps, &pa, &up, &sp, &ha, &l1, &l2};
     // An ordinary launch: with one block per compute unit and nothing else on the device
-    // every block is resident at once, which is what the exchange needs; a block that has to
-    // wait for a compute unit delays its cluster, and the bounded waits cover that.
-    // (A cooperative launch would state the requirement to the runtime, at 20 us per launch.)
-    e = hipLaunchKernel(kern, dim3(nclusters * parts), dim3(512), args, lds, s);
-    if (e == hipSuccess) *ran = true;
-    return e;
+    // every block is resident at once.  Only the blocks of one cluster depend on each other,
+    // and blocks start in index order, so when other work holds compute units the clusters
+    // that are complete run to the end and make room; a cluster that is half resident waits
+    // for its other half within the bound of its polls (about a second, against well under a
+    // millisecond for the whole kernel).  (A cooperative launch would state the requirement
+    // to the runtime; it costs 20 us per launch here.)
+    return hipLaunchKernel(kern, dim3(nclusters * parts), dim3(512), args, lds, s);
   });
 }
 
