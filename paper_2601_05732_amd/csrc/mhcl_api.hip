@@ -173,9 +173,11 @@ int run_fwd_coeffs_pre(const mhcl_desc &d, const void *x, const float *W, const 
   if (once && fwd_once_ok(d)) {
     OnceWs w(d, ws);
     bool usable = false;
-    MHCL_HIP(prepare_fwd_once(d, logits(d), w, s, &usable));
+    MHCL_HIP(prepare_fwd_once(d, logits(d), &usable));
     if (usable) {
-      MHCL_HIP(launch_pack_w_b(d, logits(d), W, w.Wp, s));
+      // (the exchange rings are zeroed by the launch that packs W)
+      MHCL_HIP(launch_pack_w_b(d, logits(d), W, w.Wp, s, reinterpret_cast<float *>(w.xchg),
+                               w.xchg_words * 2));
       {
         StageBracket br(MHCL_STAGE_FWD_PROJ, s);
         MHCL_HIP(launch_fwd_once(d, logits(d), x, b, alpha, w, h, s));

@@ -40,9 +40,13 @@ __device__ __forceinline__ void pack_w_b_thread(int idx, const float *__restrict
   Wp[(static_cast<size_t>(blk) * 2 + 1) * 64 + lane] = vl;
 }
 
+// Also clears `nzero` floats at `zero` (grid-stride): scratch that the kernel launched after
+// this one expects to start from zero, without a launch of its own.
 __global__ __launch_bounds__(256) void pack_w_b_kernel(const float *__restrict__ W, int K, int M,
-                                                       int NT, uint4 *__restrict__ Wp) {
+                                                       int NT, uint4 *__restrict__ Wp,
+                                                       float *__restrict__ zero, unsigned nzero) {
   pack_w_b_thread(blockIdx.x * 256 + threadIdx.x, W, K, M, NT, Wp);
+  for (unsigned i = blockIdx.x * 256 + threadIdx.x; i < nzero; i += gridDim.x * 256) zero[i] = 0.f;
 }
 
 // ---------------------------------------------------------------------------
@@ -1685,11 +1689,13 @@ bool fast_path_ok(const mhcl_desc &d) {
 
 size_t packed_w_b_bytes(const mhcl_desc &d, int M) { return packed_b_bytes(d.n * d.C, M); }
 
-hipError_t launch_pack_w_b(const mhcl_desc &d, int M, const float *W, void *Wp, hipStream_t s) {
+hipError_t launch_pack_w_b(const mhcl_desc &d, int M, const float *W, void *Wp, hipStream_t s,
+                           float *zero, size_t nzero) {
   const int K = d.n * d.C, NT = logit_tiles(M);
   const int threads = (K / 32) * NT * 64;
+  if (nzero > 0xffffffffu) return hipErrorInvalidValue;
   hipLaunchKernelGGL(pack_w_b_kernel, dim3((threads + 255) / 256), dim3(256), 0, s, W, K, M, NT,
-                     static_cast<uint4 *>(Wp));
+                     static_cast<uint4 *>(Wp), zero, static_cast<unsigned>(nzero));
   return hipGetLastError();
 }
 

@@ -149,6 +149,55 @@ __global__ __launch_bounds__(128) void coeffs_epilogue_kernel(
   for (int j = 0; j < N; ++j) { H_pre[t * N + j] = Hp[j]; H_post[t * N + j] = Hq[j]; }
 }
 
+// The same for many slices (at most 32 logits, M a multiple of 4): one thread per token would
+// read them in as many dependent rounds, one logit at a time.  Here eight lanes share a token,
+// lane c adds logits 4c..4c+3 of all slices in order (16-byte loads, a token's row of a slice
+// is one contiguous request), the sums meet in LDS and one thread per token goes on.
+// Same order of additions as coeffs_epilogue_kernel, so the same bits.
+template <int N, int MODE>
+__global__ __launch_bounds__(256) void coeffs_epilogue_sliced_kernel(
+    const float *__restrict__ u_raw, const float *__restrict__ sumsq, int parts,
+    const float *__restrict__ b, const float *__restrict__ alpha, int nC, float eps, int sk_iters,
+    int64_t T, float *__restrict__ H_res, float *__restrict__ H_pre, float *__restrict__ H_post) {
+  constexpr int R = Dims<N, MODE>::R, M = Dims<N, MODE>::M;
+  static_assert(M % 4 == 0 && M <= 32, "rows of 16-byte pieces, eight lanes per token");
+  __shared__ float su[32][M + 1];   // 32 tokens per block: M sums and the sum of squares
+  const int tl = threadIdx.x >> 3, c = threadIdx.x & 7;
+  const int64_t t0 = static_cast<int64_t>(blockIdx.x) * 32;
+  int64_t t = t0 + tl;
+  if (t > T - 1) t = T - 1;
+  if (c < M / 4) {
+    const float4 *row = reinterpret_cast<const float4 *>(u_raw + t * M) + c;
+    const size_t stride = static_cast<size_t>(T) * M / 4;   // float4 per slice
+    float4 acc = row[0];
+    for (int pt = 1; pt < parts; ++pt) {
+      const float4 v = row[pt * stride];
+      acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+    }
+    su[tl][4 * c + 0] = acc.x; su[tl][4 * c + 1] = acc.y;
+    su[tl][4 * c + 2] = acc.z; su[tl][4 * c + 3] = acc.w;
+  }
+  if (c == 7) {   // (the lane with the fewest logits to add, or none)
+    float ssq = sumsq[t];
+    for (int pt = 1; pt < parts; ++pt) ssq += sumsq[pt * T + t];
+    su[tl][M] = ssq;
+  }
+  __syncthreads();
+  if (threadIdx.x >= 32) return;
+  t = t0 + threadIdx.x;
+  if (t >= T) return;
+  float u[M], bb[M], a[R], Hr[N * N], Hp[N], Hq[N];
+#pragma unroll
+  for (int m = 0; m < M; ++m) { u[m] = su[threadIdx.x][m]; bb[m] = b[m]; }
+  const float ssq = su[threadIdx.x][M];
+  const TokenParams p{alpha[0], alpha[1], alpha[2], eps, sk_iters};
+  token_coeffs<N, MODE>(u, ssq, nC, bb, p, Hr, Hp, Hq, a);
+#pragma unroll
+  for (int e = 0; e < N * N; ++e) H_res[t * N * N + e] = Hr[e];
+#pragma unroll
+  for (int j = 0; j < N; ++j) { H_pre[t * N + j] = Hp[j]; H_post[t * N + j] = Hq[j]; }
+}
+
 template <int N, int MODE>
 __global__ __launch_bounds__(128) void coeffs_bwd_epilogue_kernel(
     const float *__restrict__ u_raw, const float *__restrict__ sumsq, int parts,
@@ -634,6 +683,15 @@ hipError_t launch_coeffs_epilogue(const mhcl_desc &d, int parts, const float *u_
   return dispatch_n5(d.n, [&](auto nn) {
     return dispatch_mode(d.res_mode, [&](auto mm) {
       constexpr int N = decltype(nn)::value, MODE = decltype(mm)::value;
+      constexpr int M = Dims<N, MODE>::M;
+      if constexpr (M % 4 == 0 && M <= 32) {
+        if (parts >= 8) {
+          hipLaunchKernelGGL((coeffs_epilogue_sliced_kernel<N, MODE>), dim3(blocks_for(d.T, 32)),
+                             dim3(256), 0, s, u_raw, sumsq, parts, b, alpha, d.n * d.C, d.eps,
+                             d.sk_iters, d.T, H_res, H_pre, H_post);
+          return hipGetLastError();
+        }
+      }
       hipLaunchKernelGGL((coeffs_epilogue_kernel<N, MODE>), dim3(blocks_for(d.T, 128)), dim3(128),
                          0, s, u_raw, sumsq, parts, b, alpha, d.n * d.C, d.eps, d.sk_iters, d.T,
                          H_res, H_pre, H_post);

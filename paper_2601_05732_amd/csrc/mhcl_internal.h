@@ -108,7 +108,9 @@ bool fast_path_ok(const mhcl_desc &d);
 constexpr int kMaxKSplit = 4;
 int proj_ksplit(const mhcl_desc &d);
 size_t packed_w_b_bytes(const mhcl_desc &d, int M);
-hipError_t launch_pack_w_b(const mhcl_desc &d, int M, const float *W, void *Wp, hipStream_t s);
+// packs W (B layout) and, in the same launch, clears `nzero` floats at `zero`
+hipError_t launch_pack_w_b(const mhcl_desc &d, int M, const float *W, void *Wp, hipStream_t s,
+                           float *zero = nullptr, size_t nzero = 0);
 hipError_t launch_proj_mfma(const mhcl_desc &d, int M, const void *x, const void *Wp, float *u_raw,
                             float *sumsq, hipStream_t s);
 
@@ -123,11 +125,11 @@ struct OnceWs {
   int parts;
   OnceWs(const mhcl_desc &d, void *ws);
 };
-// Before the kernel: *usable == false on return with hipSuccess means that this device
-// cannot hold the kernel's grid at once (the caller then takes the two-kernel path);
-// otherwise the exchange rings have been zeroed on `s`.
-hipError_t prepare_fwd_once(const mhcl_desc &d, int M, const OnceWs &w, hipStream_t s, bool *usable);
-// the kernel itself; w.Wp must hold the packed W
+// *usable == false on return with hipSuccess: this device cannot hold the kernel's grid at
+// once (the caller then takes the two-kernel path).
+hipError_t prepare_fwd_once(const mhcl_desc &d, int M, bool *usable);
+// the kernel itself; w.Wp must hold the packed W and the w.xchg_words words at w.xchg must be
+// zero (tags count from 1 in every launch)
 hipError_t launch_fwd_once(const mhcl_desc &d, int M, const void *x, const float *b,
                            const float *alpha, const OnceWs &w, void *h, hipStream_t s);
 

@@ -241,12 +241,25 @@ __global__ __launch_bounds__(512, 1) void fwd_once_kernel(
     }
     // ---- B: H_pre of this block's share of group ib from the parts' sums, in part order
     if (wave == 7 && doB) {
+      // (in part order, as the coefficient stage adds the slices: that is what makes h agree
+      //  with the H_pre the call returns; four parts are read from LDS at a time so that the
+      //  reads overlap, the additions stay one chain; parts is 4, 8 or 16.  This stage is on
+      //  the step's critical path, the other waves wait for it at the barrier below: with one
+      //  read per part and addition the kernel took 0.07 ms longer; moving the parts' values
+      //  between lanes with DPP row shifts instead of re-reading LDS was slower again.)
       float tot[NV];
+      for (int p0 = 0; p0 < parts; p0 += 4) {
+        float v[4][NV];
 #pragma unroll
-      for (int k = 0; k < NV; ++k) tot[k] = xw[(btk * parts) * NV + k];
-      for (int p = 1; p < parts; ++p) {
+        for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int k = 0; k < NV; ++k) tot[k] += xw[(btk * parts + p) * NV + k];
+          for (int k = 0; k < NV; ++k) v[i][k] = xw[(btk * parts + p0 + i) * NV + k];
+#pragma unroll
+        for (int k = 0; k < NV; ++k) tot[k] = p0 == 0 ? v[0][k] : tot[k] + v[0][k];
+#pragma unroll
+        for (int i = 1; i < 4; ++i)
+#pragma unroll
+          for (int k = 0; k < NV; ++k) tot[k] += v[i][k];
       }
       if (lane < 16 && bp < N) {
         float u = tot[1];
@@ -358,7 +371,7 @@ OnceWs::OnceWs(const mhcl_desc &d, void *ws) {
   bytes = c.off;
 }
 
-hipError_t prepare_fwd_once(const mhcl_desc &d, int M, const OnceWs &w, hipStream_t s, bool *usable) {
+hipError_t prepare_fwd_once(const mhcl_desc &d, int M, bool *usable) {
   *usable = false;
   return dispatch_once(d.n, logit_tiles(M), [&](auto nn, auto nt) {
     constexpr int N = decltype(nn)::value, NT = decltype(nt)::value;
@@ -366,8 +379,7 @@ hipError_t prepare_fwd_once(const mhcl_desc &d, int M, const OnceWs &w, hipStrea
     static std::atomic<int> cache[kOnceMaxDevices];   // zero-initialised
     if (!device_takes_once(kern, OnceCfg<N, NT>::kLdsBytes, cache)) return hipSuccess;
     *usable = true;
-    // exchange rings start from zero: tags count from 1 in every launch
-    return launch_fill_zero(reinterpret_cast<float *>(w.xchg), w.xchg_words * 2, s);
+    return hipSuccess;
   });
 }
 

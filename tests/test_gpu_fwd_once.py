@@ -69,6 +69,12 @@ def test_single_read_forward_matches_oracle_and_separable_calls(wl):
         rs = to_np64(got["H_res"]).sum(-1)
         cs = to_np64(got["H_res"]).sum(-2)
         assert np.abs(rs - 1).max() <= 1e-6 and np.abs(cs - 1).max() <= 1e-6
+    # h was made with the H_pre the call returns: the kernel adds the parts' sums in the order
+    # the coefficient stage adds the slices, and mixes like mhcl_pre
+    h2 = torch.empty_like(got["h"])
+    mhcl.mhcl_pre(d, inp["x"], got["H_pre"], h2)
+    torch.cuda.synchronize()
+    assert torch.equal(h2, got["h"]), "h is not H_pre x of the returned H_pre, bit for bit"
     # a second call on the same workspace: the same bits
     L.forward_fused()
     torch.cuda.synchronize()
