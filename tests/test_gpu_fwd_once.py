@@ -99,3 +99,77 @@ def test_shapes_outside_keep_the_two_kernel_path():
         inp = si.make_inputs(wl, seed=0, device="cuda")
         L = GpuLayer(desc_for(wl), inp)
         assert _pre_stage_recorded(L), wl.name
+
+
+def _guarded(nbytes, guard=1 << 16):
+    buf = torch.full((nbytes + 2 * guard + 256,), 0xA5, dtype=torch.uint8, device="cuda")
+    off = guard + ((-(buf.data_ptr() + guard)) % 256)
+    return buf, buf[off:off + nbytes], off
+
+
+def test_single_read_forward_stays_inside_its_buffers():
+    """Outputs and a workspace of exactly mhcl_workspace_bytes between guard regions."""
+    wl = si.Workload("once_guard", n=4, C=2048, T=16384 + 5, io="bf16", backward=False)
+    inp = si.make_inputs(wl, seed=5, device="cuda")
+    d = desc_for(wl)
+    L = GpuLayer(d, inp)
+    guards = []
+    for k in ("H_res", "H_pre", "H_post", "h"):
+        t = getattr(L, k)
+        nb = t.numel() * t.element_size()
+        buf, view, off = _guarded(nb)
+        setattr(L, k, view.view(t.dtype).view(t.shape))
+        guards.append((k, buf, off, nb))
+    nb = mhcl.workspace_bytes(d, mhcl.OP_FWD_COEFFS_PRE)
+    buf, L.ws, off = _guarded(nb)
+    guards.append(("ws", buf, off, nb))
+    mhcl.mhcl_fwd_coeffs_pre(d, inp["x"], inp["W"], inp["b"], inp["alpha"], L.H_res, L.H_pre, L.H_post,
+                             L.h, L.ws)
+    torch.cuda.synchronize()
+    for k, buf, off, nb in guards:
+        assert bool((buf[:off] == 0xA5).all()) and bool((buf[off + nb:] == 0xA5).all()), k
+    assert bool(torch.isfinite(L.h.float()).all())
+
+
+def test_single_read_forward_in_a_graph_and_on_two_streams():
+    """The kernel is an ordinary launch: it can be captured, and two calls on two streams (own
+    outputs and workspaces) may overlap: each has 256 blocks that want a compute unit of their
+    own, so they share the device cluster by cluster; both must come out bit for bit."""
+    wl = si.Workload("once_graph", n=4, C=4096, T=8192 + 3, io="bf16", backward=False)
+    inp = si.make_inputs(wl, seed=6, device="cuda")
+    d = desc_for(wl)
+    A, B = GpuLayer(d, inp), GpuLayer(d, inp)
+    names = ("H_res", "H_pre", "H_post", "h")
+    call = lambda L: mhcl.mhcl_fwd_coeffs_pre(d, inp["x"], inp["W"], inp["b"], inp["alpha"], L.H_res,
+                                              L.H_pre, L.H_post, L.h, L.ws)
+    call(A)
+    torch.cuda.synchronize()
+    want = {k: getattr(A, k).clone() for k in names}
+    # captured and replayed, with eager calls in between
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        call(A)
+    for rep in range(3):
+        for k in names:
+            getattr(A, k).fill_(float("nan"))
+        g.replay()
+        torch.cuda.synchronize()
+        for k in names:
+            assert torch.equal(getattr(A, k), want[k]), ("replay", rep, k)
+        call(B)
+        torch.cuda.synchronize()
+    # two streams at once, several rounds
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    for rep in range(4):
+        for L in (A, B):
+            for k in names:
+                getattr(L, k).fill_(float("nan"))
+        torch.cuda.synchronize()
+        with torch.cuda.stream(s1):
+            call(A)
+        with torch.cuda.stream(s2):
+            call(B)
+        torch.cuda.synchronize()
+        for L in (A, B):
+            for k in names:
+                assert torch.equal(getattr(L, k), want[k]), ("two streams", rep, k)
