@@ -88,8 +88,9 @@ __device__ __forceinline__ void finish_words(const u64 *p, unsigned tag, u64 (&w
 }
 
 // Barrier for data exchanged through LDS only: this wave's LDS operations are done, its
-// outstanding loads from memory stay in flight (__syncthreads() would wait for them too: its
-// release fence covers global memory).
+// outstanding loads and stores stay in flight.  (Written out so that no fence on global memory
+// can come with it; for this kernel the compiler emits the same two instructions for
+// __syncthreads().)
 __device__ __forceinline__ void lds_barrier() {
   __builtin_amdgcn_sched_barrier(0);
   asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" : : : "memory");
