@@ -173,3 +173,38 @@ def test_single_read_forward_in_a_graph_and_on_two_streams():
         for L in (A, B):
             for k in names:
                 assert torch.equal(getattr(L, k), want[k]), ("two streams", rep, k)
+
+
+def test_single_read_forward_seeded_shapes_against_the_separable_calls():
+    """Seeded shapes and forms around the smallest token counts the kernel takes (every ragged
+    tail 1..15 of the last 16-token group at least once over the cases): coefficients against
+    mhcl_coeffs, h against mhcl_pre of the returned H_pre bit for bit."""
+    import random
+    rng = random.Random(17)
+    for case in range(14):
+        C = rng.choice([1024, 2048, 4096])
+        mode = rng.choice(["lite", "lite", "sk", "subset"])
+        n = rng.choice([2, 3, 4])
+        K = 0
+        if mode == "subset":
+            K = rng.randint(1, min(32 - 2 * n, [0, 1, 2, 6, 24][n]))
+        T = 32 * 16 * (256 // (C // 256)) + rng.randint(0, 700) * 16 + (case % 15 + 1)
+        wl = si.Workload(f"once_fuzz{case}", n=n, C=C, T=T, io="bf16", res_mode=mode, n_perm=K,
+                         backward=False)
+        print(f"case {wl}", flush=True)
+        inp = si.make_inputs(wl, seed=100 + case, device="cuda")
+        d = desc_for(wl, perm=inp.get("perm"))
+        L = GpuLayer(d, inp)
+        assert not _pre_stage_recorded(L), wl
+        got = {k: getattr(L, k).clone() for k in ("H_res", "H_pre", "H_post", "h")}
+        assert all(bool(torch.isfinite(v.float()).all()) for v in got.values()), wl
+        h2 = torch.empty_like(got["h"])
+        mhcl.mhcl_pre(d, inp["x"], got["H_pre"], h2)
+        mhcl.mhcl_coeffs(d, inp["x"], inp["W"], inp["b"], inp["alpha"], L.H_res, L.H_pre, L.H_post, L.ws)
+        torch.cuda.synchronize()
+        assert torch.equal(h2, got["h"]), wl
+        for k in ("H_res", "H_pre", "H_post"):
+            err = rel_err(to_np64(getattr(L, k)), to_np64(got[k]))
+            assert err <= 2e-5, (wl, k, err)
+        del L, inp, got, h2
+        torch.cuda.empty_cache()
