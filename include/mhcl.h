@@ -151,6 +151,8 @@ int mhcl_post(const mhcl_desc *desc, const void *x, const void *y, const float *
  * projection, H_pre and h from the same register tile (groups of 16 tokens
  * shared by C / 256 thread blocks that exchange their partial sums; needs the
  * 256 compute units of the device free for its 256 blocks, see the source).
+ * Its workspace holds one slice of the projection per 256 columns,
+ * (C / 256) * T * (M + 1) * 4 bytes (6 % of x at n = 4, C = 4096).
  * The projection's sum over n C terms is then split differently from
  * mhcl_coeffs, so H_* agree with it to fp32 rounding of the logits and h to
  * one bf16 step.  Every other shape, or a device that cannot hold the 256
