@@ -114,3 +114,22 @@ def test_subset_descriptor_fields_are_validated_on_the_host():
     assert mhcl.lib().mhcl_validate(ctypes.byref(d.c)) == 1
     full = mhcl.Desc(6, 64, 16)                                      # n = 6 only in the subset form
     assert mhcl.lib().mhcl_validate(ctypes.byref(full.c)) == 1
+
+
+def test_workspace_of_the_fused_forward_follows_the_header():
+    """mhcl_fwd_coeffs_pre: where the single-read kernel applies (bf16, at most 32 logits,
+    C in {1024, 2048, 4096}, at least 512 * 65536 / C tokens) the workspace holds one slice of
+    the projection per 256 columns; everywhere else it is the workspace of mhcl_coeffs."""
+    def sizes(n, C, T, io=mhcl.BF16, res_mode=mhcl.RES_LITE):
+        d = mhcl.Desc(n, C, T, io, res_mode=res_mode)
+        return d, mhcl.workspace_bytes(d, mhcl.OP_FWD_COEFFS_PRE), mhcl.workspace_bytes(d, mhcl.OP_COEFFS)
+    for n, C, T in ((4, 4096, 32768), (4, 4096, 8192), (3, 1024, 65536), (2, 2048, 16384)):
+        d, fused, plain = sizes(n, C, T)
+        slices = (C // 256) * T * (d.M + 1) * 4
+        assert fused > plain and slices <= fused <= slices + (8 << 20), (n, C, T, fused, slices)
+    for n, C, T, io, mode in ((4, 4096, 8191, mhcl.BF16, mhcl.RES_LITE),     # too few tokens
+                              (4, 4096 + 256, 32768, mhcl.BF16, mhcl.RES_LITE),  # another C
+                              (5, 1024, 65536, mhcl.BF16, mhcl.RES_LITE),    # 130 logits
+                              (4, 4096, 32768, mhcl.F32, mhcl.RES_LITE)):    # f32 streams
+        _, fused, plain = sizes(n, C, T, io, mode)
+        assert fused == plain, (n, C, T)
