@@ -146,8 +146,8 @@ int mhcl_post(const mhcl_desc *desc, const void *x, const void *y, const float *
               const float *H_post, void *x_out, void *stream);
 
 /* mhcl_coeffs and mhcl_pre in one call (one validation, one workspace).
- * bf16 streams with at most 32 logits, C in {1024, 2048, 4096} and at least
- * 512 * 65536 / C tokens: ONE kernel reads x from HBM once and produces the
+ * bf16 streams with at most 32 logits, C a multiple of 256 from 1024 to 8192
+ * and at least 512 * floor(65536 / C) tokens: ONE kernel reads x from HBM once and produces the
  * projection, H_pre and h from the same register tile (groups of 16 tokens
  * shared by C / 256 thread blocks that exchange their partial sums; needs the
  * 256 compute units of the device free for its 256 blocks, see the source).

@@ -115,7 +115,7 @@ hipError_t launch_proj_mfma(const mhcl_desc &d, int M, const void *x, const void
                             float *sumsq, hipStream_t s);
 
 // Single-read forward (projection slices, H_pre and h from one read of x): bf16 fast path
-// with at most 32 logits, C in {1024, 2048, 4096}, enough tokens to fill the pipeline.
+// with at most 32 logits, C a multiple of 256 from 1024 to 8192, enough tokens to fill the pipeline.
 bool fwd_once_ok(const mhcl_desc &d);
 struct OnceWs {
   float *u_part, *sumsq_part;   // [parts][T][M], [parts][T]: one slice per 256-column part

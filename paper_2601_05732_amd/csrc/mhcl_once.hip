@@ -10,8 +10,8 @@
 //      the partial sum of squares as slice `part` of u_raw / sumsq (the coefficient stage
 //      adds the slices in order, as it does for a K split),
 //      publishes its partial pre-logits and sum of squares to the cluster,
-//   B  three groups later, adds those of ITS share of the group's tokens (16 / parts of them)
-//      over all parts, in part order, and publishes H_pre of those tokens,
+//   B  three groups later, adds those of ITS share of the group's tokens (token t belongs to
+//      part t mod parts) over all parts, in part order, and publishes H_pre of those tokens,
 //   C  another three groups later, reads H_pre of all 16 tokens and writes its 256 columns of
 //      h from the piece it still holds (eight pieces in registers, 16 registers each at n = 4).
 // The blocks of a cluster exchange those few values through memory as 64-bit words that carry
@@ -52,7 +52,10 @@ struct OnceCfg {
   static constexpr int kSteps = N * (kOnceCB / 32);                // K steps of the block's W slice
   static constexpr int kWVec = kSteps * NT * 2 * 64;               // u32x4
   static constexpr int kRedVec = 8 * (NT + 1) * 64;                // f32x4: [wave][tile][lane]
-  static constexpr int kLdsBytes = (kWVec + kRedVec) * 16 + kOnceGT * (3 * N + 2) * 4;
+  // exchange words of a step: at most 64 (token, part) pairs of NV values (a block's tokens
+  // times the parts, 4 to 32 of them: 32 at most) and the group's 16 N values of H_pre
+  static constexpr int kXwFloats = 64 * NV + kOnceGT * N;
+  static constexpr int kLdsBytes = (kWVec + kRedVec) * 16 + (kXwFloats + kOnceGT * NV) * 4;
 };
 
 __device__ __forceinline__ void put_word(u64 *p, float v, unsigned tag) {
@@ -110,7 +113,7 @@ __global__ __launch_bounds__(512, 1) void fwd_once_kernel(
   u32x4 *wl = lds;                                                  // [kSteps][NT][2][64]
   f32x4 *red = reinterpret_cast<f32x4 *>(lds + Cfg::kWVec);         // [8 waves][NT + 1][64]
   float *xw = reinterpret_cast<float *>(red + Cfg::kRedVec);        // exchange words of the step: [16][NV], then H_pre [16][N]
-  float *pub = xw + kOnceGT * (2 * N + 1);                          // [16][NV]: this block's sums of the step's group
+  float *pub = xw + Cfg::kXwFloats;                                  // [16][NV]: this block's sums of the step's group
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;       // wave = column group of 32
   const int r = lane & 15, q = lane >> 4;
   const int part = blockIdx.x % parts, cluster = blockIdx.x / parts;
@@ -145,22 +148,26 @@ __global__ __launch_bounds__(512, 1) void fwd_once_kernel(
   auto l2_at = [&](int it, int tok) {
     return l2 + ((static_cast<size_t>(it % kOnceXR) * nclusters + cluster) * kOnceGT + tok) * N;
   };
-  // B: wave 7, lane l = lane % 16 -> (token tk of this block's share, part p); the other
-  // lanes repeat lanes 0..15 and publish nothing
-  const int tpb = kOnceGT / parts;                       // tokens of a group this block reduces
-  const int bl = lane & 15, btk = bl / parts, bp = bl % parts;
-  const int btok = part * tpb + btk;
-  // Polling: what a block reads per step is 16 NV words of l1 (its tokens from every part)
-  // and 16 N words of l2 (H_pre of the group); every wave polls an equal share, ONE word per
-  // lane, so each wave issues exactly one poll load per step.
-  constexpr int kBWords = kOnceGT * NV, kWords = kBWords + kOnceGT * N, kPerWave = kWords / 8;
-  static_assert(kWords % 8 == 0 && kPerWave <= 64, "poll words are split evenly over the waves");
-  const int pw = wave * kPerWave + (lane < kPerWave ? lane : kPerWave - 1);   // this lane's word
+  // B: block `part` reduces the tokens t of a group with t % parts == part: `nown` of them
+  // (none for part >= 16).  Wave 7, lane o N + j -> H_pre[j] of its o-th token.
+  constexpr int kPubWords = kOnceGT * NV;                 // what a block publishes per group
+  const int nown = part < kOnceGT ? (kOnceGT - 1 - part) / parts + 1 : 0;
+  const int bo = (lane / N) < nown ? lane / N : 0, bj = lane % N;
+  const bool bpub = lane < nown * N;
+  const int btok = part + bo * parts;
+  // Polling: what a block reads per step is nown * parts * NV words of l1 (its tokens from
+  // every part) and 16 N words of l2 (H_pre of the group); the waves poll equal shares, ONE
+  // word per lane, so each wave issues exactly one poll load per step.
+  const int kBWords = nown * parts * NV, kWords = kBWords + kOnceGT * N;
+  const int kPerWave = (kWords + 7) / 8;                  // <= 64 lanes: parts <= 32
+  const int pwi = wave * kPerWave + (lane < kPerWave ? lane : kPerWave - 1);
+  const bool pw_live = lane < kPerWave && pwi < kWords;
+  const int pw = pwi < kWords ? pwi : kWords - 1;         // this lane's word (past the end: the last one again)
   const bool pw_b = pw < kBWords;
-  // word pw < kBWords is value k of part p for token tk of this block's share: pw = (tk parts + p) NV + k
-  const int pw_k = pw % NV, pw_p = (pw / NV) % parts, pw_tk = pw / (NV * parts);
+  // word pw < kBWords is value k of part p for the o-th token of this block: pw = (o parts + p) NV + k
+  const int pw_k = pw % NV, pw_p = (pw / NV) % parts, pw_tok = part + (pw / (NV * parts)) * parts;
 
-  const float alpha_pre = alpha[1], b_pre = b[R + (bp < N ? bp : 0)];
+  const float alpha_pre = alpha[1], b_pre = b[R + bj];
   u32x4 P[kOnceRing][N];
   bool bad = false;
   u64 nw[1] = {};            // first try of the word this lane consumes in the next step
@@ -183,7 +190,7 @@ __global__ __launch_bounds__(512, 1) void fwd_once_kernel(
     {
       const int nb = ib + 1, nc = ic + 1;
       nvalid = pw_b ? (nb >= 0 && nb < niter) : (nc >= 0 && nc < niter);
-      np = !nvalid ? l1 : (pw_b ? l1_at(nb, part * tpb + pw_tk, pw_p) + pw_k : l2_at(nc, 0) + (pw - kBWords));
+      np = !nvalid ? l1 : (pw_b ? l1_at(nb, pw_tok, pw_p) + pw_k : l2_at(nc, 0) + (pw - kBWords));
       nw[0] = get_word(np);
     }
     load_piece(Pn, it + PF);   // unconditional (past the last group: clamped re-reads, never used)
@@ -215,7 +222,7 @@ __global__ __launch_bounds__(512, 1) void fwd_once_kernel(
       float v[1] = {0.f};
       if (wvalid)
         finish_words<1>(wp, static_cast<unsigned>(pw_b ? ib : ic) + 1u, w, v, bad);
-      if (lane < kPerWave) xw[pw] = v[0];
+      if (pw_live) xw[pw] = v[0];
     }
     lds_barrier();
     if (doA && wave < NT + 1) {   // wave k adds tile k over the eight column groups, in order
@@ -244,31 +251,30 @@ __global__ __launch_bounds__(512, 1) void fwd_once_kernel(
     if (wave == 7 && doB) {
       // (in part order, as the coefficient stage adds the slices: that is what makes h agree
       //  with the H_pre the call returns; four parts are read from LDS at a time so that the
-      //  reads overlap, the additions stay one chain; parts is 4, 8 or 16.  This stage is on
-      //  the step's critical path, the other waves wait for it at the barrier below: with one
-      //  read per part and addition the kernel took 0.07 ms longer; moving the parts' values
-      //  between lanes with DPP row shifts instead of re-reading LDS was slower again.)
-      float tot[NV];
+      //  reads overlap, the additions stay one chain.  This stage is on the step's critical
+      //  path, the other waves wait for it at the barrier below: with one read per part and
+      //  addition the kernel took 0.07 ms longer; moving the parts' values between lanes with
+      //  DPP row shifts instead of re-reading LDS was slower again.)
+      const float *mine = xw + bo * parts * NV;   // [parts][NV] of this lane's token
+      float ssq = 0.f, u = 0.f;
       for (int p0 = 0; p0 < parts; p0 += 4) {
-        float v[4][NV];
+        float vs[4], vu[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < 4; ++i) {
+          const int pp = p0 + i < parts ? p0 + i : parts - 1;
+          vs[i] = mine[pp * NV];
+          vu[i] = mine[pp * NV + 1 + bj];
+        }
 #pragma unroll
-          for (int k = 0; k < NV; ++k) v[i][k] = xw[(btk * parts + p0 + i) * NV + k];
-#pragma unroll
-        for (int k = 0; k < NV; ++k) tot[k] = p0 == 0 ? v[0][k] : tot[k] + v[0][k];
-#pragma unroll
-        for (int i = 1; i < 4; ++i)
-#pragma unroll
-          for (int k = 0; k < NV; ++k) tot[k] += v[i][k];
+        for (int i = 0; i < 4; ++i) {
+          if (p0 + i == 0) { ssq = vs[0]; u = vu[0]; }
+          else if (p0 + i < parts) { ssq += vs[i]; u += vu[i]; }
+        }
       }
-      if (lane < 16 && bp < N) {
-        float u = tot[1];
-#pragma unroll
-        for (int j = 1; j < N; ++j) u = bp == j ? tot[1 + j] : u;
-        const float rr = 1.f / sqrtf(tot[0] / nC + eps);
+      if (bpub) {
+        const float rr = 1.f / sqrtf(ssq / nC + eps);
         const float hv = sigmoidf(alpha_pre * (rr * u) + b_pre);
-        put_word(l2_at(ib, btok) + bp, hv, static_cast<unsigned>(ib) + 1u);
+        put_word(l2_at(ib, btok) + bj, hv, static_cast<unsigned>(ib) + 1u);
       }
     }
     // ---- C: h of group ic from the piece loaded DC groups ago
@@ -296,9 +302,9 @@ __global__ __launch_bounds__(512, 1) void fwd_once_kernel(
     }
     lds_barrier();   // red and xw are rewritten by the next step
     // what this block tells its cluster about group `it`: 16 NV words, contiguous
-    if (doA && wave >= 3 && wave < 3 + (kBWords + 63) / 64) {
+    if (doA && wave >= 3 && wave < 3 + (kPubWords + 63) / 64) {
       const int i = (wave - 3) * 64 + lane;
-      if (i < kBWords) put_word(l1_at(it, 0, part) + i, pub[i], static_cast<unsigned>(it) + 1u);
+      if (i < kPubWords) put_word(l1_at(it, 0, part) + i, pub[i], static_cast<unsigned>(it) + 1u);
     }
   };
 
@@ -352,7 +358,9 @@ bool fwd_once_ok(const mhcl_desc &d) {
   if (!fast_path_ok(d)) return false;
   const int M = res_logits(d) + 2 * d.n;
   if (d.n < 2 || d.n > 4 || logit_tiles(M) > 2) return false;
-  if (d.C != 1024 && d.C != 2048 && d.C != 4096) return false;
+  // 4 to 32 parts (with 64, C = 16384, the per-token stage adds 64 parts' sums per step and
+  // the kernel is slower than the two it replaces: 0.57 against 0.45 ms at 8192 tokens)
+  if (d.C % kOnceCB != 0 || d.C < 4 * kOnceCB || d.C > 32 * kOnceCB) return false;
   // at least 32 groups per cluster: with fewer the pipeline's fill and drain (DC steps each)
   // cost more than the second read of x (measured at C = 1024: slower at 16 groups, faster at 64)
   return d.T >= 32 * static_cast<int64_t>(kOnceGT) * (kOnceBlocks / (d.C / kOnceCB));

@@ -118,17 +118,21 @@ def test_subset_descriptor_fields_are_validated_on_the_host():
 
 def test_workspace_of_the_fused_forward_follows_the_header():
     """mhcl_fwd_coeffs_pre: where the single-read kernel applies (bf16, at most 32 logits,
-    C in {1024, 2048, 4096}, at least 512 * 65536 / C tokens) the workspace holds one slice of
+    C a multiple of 256 from 1024 to 8192, at least 512 * floor(65536 / C) tokens) the workspace holds one slice of
     the projection per 256 columns; everywhere else it is the workspace of mhcl_coeffs."""
     def sizes(n, C, T, io=mhcl.BF16, res_mode=mhcl.RES_LITE):
         d = mhcl.Desc(n, C, T, io, res_mode=res_mode)
         return d, mhcl.workspace_bytes(d, mhcl.OP_FWD_COEFFS_PRE), mhcl.workspace_bytes(d, mhcl.OP_COEFFS)
-    for n, C, T in ((4, 4096, 32768), (4, 4096, 8192), (3, 1024, 65536), (2, 2048, 16384)):
+    for n, C, T in ((4, 4096, 32768), (4, 4096, 8192), (3, 1024, 65536), (2, 2048, 16384),
+                    (4, 5120, 6144), (4, 8192, 4096), (3, 1280, 26112)):
         d, fused, plain = sizes(n, C, T)
         slices = (C // 256) * T * (d.M + 1) * 4
         assert fused > plain and slices <= fused <= slices + (8 << 20), (n, C, T, fused, slices)
     for n, C, T, io, mode in ((4, 4096, 8191, mhcl.BF16, mhcl.RES_LITE),     # too few tokens
-                              (4, 4096 + 256, 32768, mhcl.BF16, mhcl.RES_LITE),  # another C
+                              (4, 4096 + 64, 32768, mhcl.BF16, mhcl.RES_LITE),   # C not a multiple of 256
+                              (4, 768, 65536, mhcl.BF16, mhcl.RES_LITE),         # fewer than four parts
+                              (2, 16384, 8192, mhcl.BF16, mhcl.RES_LITE),        # more than 32 parts
+                              (4, 5120, 6143, mhcl.BF16, mhcl.RES_LITE),         # too few tokens
                               (5, 1024, 65536, mhcl.BF16, mhcl.RES_LITE),    # 130 logits
                               (4, 4096, 32768, mhcl.F32, mhcl.RES_LITE)):    # f32 streams
         _, fused, plain = sizes(n, C, T, io, mode)

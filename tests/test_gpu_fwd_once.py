@@ -27,6 +27,11 @@ CASES = [
     si.Workload("once_n2_c1024", n=2, C=1024, T=32768 + 1, io="bf16", backward=False),
     si.Workload("once_n4_c2048_k12", n=4, C=2048, T=16384 + 17, io="bf16", res_mode="subset", n_perm=12,
                 backward=False),
+    # part counts that divide neither 16 nor 256: 12 (21 clusters), 20 (12), 5 (51); and 32
+    si.Workload("once_n4_c3072", n=4, C=3072, T=10752 + 5, io="bf16", backward=False),
+    si.Workload("once_n4_c5120", n=4, C=5120, T=6144 + 11, io="bf16", backward=False),
+    si.Workload("once_n3_c1280", n=3, C=1280, T=26112 + 3, io="bf16", backward=False),
+    si.Workload("once_n4_c8192", n=4, C=8192, T=4096 + 9, io="bf16", backward=False),
 ]
 
 
@@ -95,6 +100,7 @@ def test_single_read_forward_matches_oracle_and_separable_calls(wl):
 def test_shapes_outside_keep_the_two_kernel_path():
     for wl in (si.Workload("small_t", n=4, C=4096, T=8192 - 16, io="bf16"),
                si.Workload("odd_c", n=4, C=4096 + 64, T=8192, io="bf16"),
+               si.Workload("wide_c", n=2, C=16384, T=4096, io="bf16"),
                si.Workload("n5", n=5, C=1024, T=16384, io="bf16")):
         inp = si.make_inputs(wl, seed=0, device="cuda")
         L = GpuLayer(desc_for(wl), inp)
@@ -181,14 +187,14 @@ def test_single_read_forward_seeded_shapes_against_the_separable_calls():
     mhcl_coeffs, h against mhcl_pre of the returned H_pre bit for bit."""
     import random
     rng = random.Random(17)
-    for case in range(14):
-        C = rng.choice([1024, 2048, 4096])
+    for case in range(18):
+        C = rng.choice([1024, 2048, 4096, 1536, 2560, 6144, 7168])
         mode = rng.choice(["lite", "lite", "sk", "subset"])
         n = rng.choice([2, 3, 4])
         K = 0
         if mode == "subset":
             K = rng.randint(1, min(32 - 2 * n, [0, 1, 2, 6, 24][n]))
-        T = 32 * 16 * (256 // (C // 256)) + rng.randint(0, 700) * 16 + (case % 15 + 1)
+        T = 32 * 16 * (256 // (C // 256)) + rng.randint(0, 300) * 16 + (case % 15 + 1)
         wl = si.Workload(f"once_fuzz{case}", n=n, C=C, T=T, io="bf16", res_mode=mode, n_perm=K,
                          backward=False)
         print(f"case {wl}", flush=True)
