@@ -152,44 +152,65 @@ __global__ __launch_bounds__(128) void coeffs_epilogue_kernel(
 // The same for many slices (at most 32 logits, M a multiple of 4): one thread per token would
 // read them in as many dependent rounds, one logit at a time.  Here eight lanes share a token,
 // lane c adds logits 4c..4c+3 of all slices in order (16-byte loads, a token's row of a slice
-// is one contiguous request), the sums meet in LDS and one thread per token goes on.
+// is one contiguous request), the sums meet in LDS and one thread per token goes on: the 64
+// tokens of a block in ONE full wave, a different one from block to block (a half-filled wave
+// costs the same issue slots as a full one, and wave w of every block sits on the same SIMD:
+// with 32 tokens per block in wave 0 this stage took 17 of the kernel's 22 us, now 4).
 // Same order of additions as coeffs_epilogue_kernel, so the same bits.
 template <int N, int MODE>
-__global__ __launch_bounds__(256) void coeffs_epilogue_sliced_kernel(
+__global__ __launch_bounds__(512) void coeffs_epilogue_sliced_kernel(
     const float *__restrict__ u_raw, const float *__restrict__ sumsq, int parts,
     const float *__restrict__ b, const float *__restrict__ alpha, int nC, float eps, int sk_iters,
     int64_t T, float *__restrict__ H_res, float *__restrict__ H_pre, float *__restrict__ H_post) {
   constexpr int R = Dims<N, MODE>::R, M = Dims<N, MODE>::M;
   static_assert(M % 4 == 0 && M <= 32, "rows of 16-byte pieces, eight lanes per token");
-  __shared__ float su[32][M + 1];   // 32 tokens per block: M sums and the sum of squares
+  __shared__ float su[64][M + 1];   // 64 tokens per block: M sums and the sum of squares
   const int tl = threadIdx.x >> 3, c = threadIdx.x & 7;
-  const int64_t t0 = static_cast<int64_t>(blockIdx.x) * 32;
+  const int64_t t0 = static_cast<int64_t>(blockIdx.x) * 64;
   int64_t t = t0 + tl;
   if (t > T - 1) t = T - 1;
   if (c < M / 4) {
     const float4 *row = reinterpret_cast<const float4 *>(u_raw + t * M) + c;
     const size_t stride = static_cast<size_t>(T) * M / 4;   // float4 per slice
-    float4 acc = row[0];
-    for (int pt = 1; pt < parts; ++pt) {
-      const float4 v = row[pt * stride];
-      acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+    // (eight slices requested at a time, added in order: a loop of one load and one addition
+    //  pays a memory round trip per slice)
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int p0 = 0; p0 < parts; p0 += 8) {
+      float4 v[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) v[i] = row[(p0 + i < parts ? p0 + i : parts - 1) * stride];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        if (p0 + i == 0) acc = v[0];
+        else if (p0 + i < parts) { acc.x += v[i].x; acc.y += v[i].y; acc.z += v[i].z; acc.w += v[i].w; }
+      }
     }
     su[tl][4 * c + 0] = acc.x; su[tl][4 * c + 1] = acc.y;
     su[tl][4 * c + 2] = acc.z; su[tl][4 * c + 3] = acc.w;
   }
   if (c == 7) {   // (the lane with the fewest logits to add, or none)
-    float ssq = sumsq[t];
-    for (int pt = 1; pt < parts; ++pt) ssq += sumsq[pt * T + t];
+    float ssq = 0.f;
+    for (int p0 = 0; p0 < parts; p0 += 8) {
+      float v[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) v[i] = sumsq[(p0 + i < parts ? p0 + i : parts - 1) * T + t];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        if (p0 + i == 0) ssq = v[0];
+        else if (p0 + i < parts) ssq += v[i];
+      }
+    }
     su[tl][M] = ssq;
   }
   __syncthreads();
-  if (threadIdx.x >= 32) return;
-  t = t0 + threadIdx.x;
+  if ((threadIdx.x >> 6) != (blockIdx.x & 7)) return;
+  const int tk = threadIdx.x & 63;
+  t = t0 + tk;
   if (t >= T) return;
   float u[M], bb[M], a[R], Hr[N * N], Hp[N], Hq[N];
 #pragma unroll
-  for (int m = 0; m < M; ++m) { u[m] = su[threadIdx.x][m]; bb[m] = b[m]; }
-  const float ssq = su[threadIdx.x][M];
+  for (int m = 0; m < M; ++m) { u[m] = su[tk][m]; bb[m] = b[m]; }
+  const float ssq = su[tk][M];
   const TokenParams p{alpha[0], alpha[1], alpha[2], eps, sk_iters};
   token_coeffs<N, MODE>(u, ssq, nC, bb, p, Hr, Hp, Hq, a);
 #pragma unroll
@@ -686,8 +707,8 @@ hipError_t launch_coeffs_epilogue(const mhcl_desc &d, int parts, const float *u_
       constexpr int M = Dims<N, MODE>::M;
       if constexpr (M % 4 == 0 && M <= 32) {
         if (parts >= 8) {
-          hipLaunchKernelGGL((coeffs_epilogue_sliced_kernel<N, MODE>), dim3(blocks_for(d.T, 32)),
-                             dim3(256), 0, s, u_raw, sumsq, parts, b, alpha, d.n * d.C, d.eps,
+          hipLaunchKernelGGL((coeffs_epilogue_sliced_kernel<N, MODE>), dim3(blocks_for(d.T, 64)),
+                             dim3(512), 0, s, u_raw, sumsq, parts, b, alpha, d.n * d.C, d.eps,
                              d.sk_iters, d.T, H_res, H_pre, H_post);
           return hipGetLastError();
         }
