@@ -158,7 +158,12 @@ int mhcl_post(const mhcl_desc *desc, const void *x, const void *y, const float *
  * one bf16 step.  Every other shape, or a device that cannot hold the 256
  * blocks at once: mhcl_coeffs followed by mhcl_pre, bit for bit (x is then
  * read twice: h needs H_pre, which needs the token's whole row).
- * Results are reproducible bit for bit from call to call either way. */
+ * Results are reproducible bit for bit from call to call either way.
+ * MHCL_FWD_ONCE=0 in the environment keeps the two-kernel form everywhere (for
+ * a process that shares the device with other long-running work: the one
+ * kernel wants a compute unit per block, waits for blocks that have none yet
+ * for about a second at most, and returns NaN in the outputs if that was not
+ * enough); it is read at every call and by mhcl_workspace_bytes. */
 int mhcl_fwd_coeffs_pre(const mhcl_desc *desc, const void *x, const float *W, const float *b,
                         const float *alpha, float *H_res, float *H_pre, float *H_post, void *h,
                         void *ws, size_t ws_bytes, void *stream);

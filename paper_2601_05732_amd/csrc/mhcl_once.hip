@@ -25,6 +25,7 @@
 #include "mhcl_internal.h"
 #include "mhcl_mfma.h"
 #include <atomic>
+#include <cstdlib>
 
 namespace mhcl {
 
@@ -356,6 +357,9 @@ bool device_takes_once(const void *kern, int lds, std::atomic<int> (&cache)[kOnc
 
 bool fwd_once_ok(const mhcl_desc &d) {
   if (!fast_path_ok(d)) return false;
+  // the caller's switch: a process that shares the device with other work for long stretches
+  // (the kernel wants a compute unit per block) can keep the two-kernel forward
+  if (const char *e = getenv("MHCL_FWD_ONCE"); e && e[0] == '0' && e[1] == 0) return false;
   const int M = res_logits(d) + 2 * d.n;
   if (d.n < 2 || d.n > 4 || logit_tiles(M) > 2) return false;
   // 4 to 32 parts (with 64, C = 16384, the per-token stage adds 64 parts' sums per step and

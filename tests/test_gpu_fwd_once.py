@@ -97,6 +97,20 @@ def test_single_read_forward_matches_oracle_and_separable_calls(wl):
     assert err <= 2 ** -7, err
 
 
+def test_environment_switch_keeps_the_two_kernel_path(monkeypatch):
+    wl = si.Workload("once_off", n=4, C=2048, T=16384, io="bf16", backward=False)
+    inp = si.make_inputs(wl, seed=2, device="cuda")
+    d = desc_for(wl)
+    on = mhcl.workspace_bytes(d, mhcl.OP_FWD_COEFFS_PRE)
+    monkeypatch.setenv("MHCL_FWD_ONCE", "0")
+    assert mhcl.workspace_bytes(d, mhcl.OP_FWD_COEFFS_PRE) == mhcl.workspace_bytes(d, mhcl.OP_COEFFS) < on
+    L = GpuLayer(d, inp)
+    assert _pre_stage_recorded(L)
+    monkeypatch.delenv("MHCL_FWD_ONCE")
+    L = GpuLayer(d, inp)
+    assert not _pre_stage_recorded(L)
+
+
 def test_shapes_outside_keep_the_two_kernel_path():
     for wl in (si.Workload("small_t", n=4, C=4096, T=8192 - 16, io="bf16"),
                si.Workload("odd_c", n=4, C=4096 + 64, T=8192, io="bf16"),
