@@ -228,3 +228,38 @@ def test_single_read_forward_seeded_shapes_against_the_separable_calls():
             assert err <= 2e-5, (wl, k, err)
         del L, inp, got, h2
         torch.cuda.empty_cache()
+
+
+def test_autograd_stack_with_and_without_the_single_read_forward(monkeypatch):
+    """Two bf16 layers through the torch.autograd front end at a shape the kernel takes: output
+    and every gradient agree with the same stack run on the two-kernel forward (the two differ
+    in how the projection's fp32 sum is split, nothing else)."""
+    from paper_2601_05732_amd.autograd import HyperConnectionStack
+    n, C, T, L = 4, 1024, 32768 + 5, 2
+    f = lambda h: torch.tanh(h.float()).to(h.dtype)
+
+    def run():
+        torch.manual_seed(0)
+        g = torch.Generator(device="cuda").manual_seed(4)
+        x0 = (torch.randn(T, C, device="cuda", generator=g)).bfloat16().requires_grad_(True)
+        G = torch.randn(T, C, device="cuda", generator=g).bfloat16()
+        stack = HyperConnectionStack(n, C, [f] * L, "lite")   # (streams take the dtype of x0)
+        for l, m in enumerate(stack.layers):
+            gg = torch.Generator(device="cuda").manual_seed(50 + l)
+            with torch.no_grad():
+                m.W.copy_(0.02 * torch.randn(m.W.shape, device="cuda", generator=gg))
+                m.b.copy_(0.1 * torch.randn(m.b.shape, device="cuda", generator=gg))
+                m.alpha.fill_(1.0)
+        out = stack(x0)
+        (out.float() * G.float()).sum().backward()
+        torch.cuda.synchronize()
+        return [out.detach().float(), x0.grad.float()] + [p.grad.float() for m in stack.layers
+                                                          for p in (m.W, m.b, m.alpha)]
+    got = run()
+    monkeypatch.setenv("MHCL_FWD_ONCE", "0")
+    ref = run()
+    names = ["out", "g_x0"] + [f"{p}{l}" for l in range(L) for p in ("g_W", "g_b", "g_alpha")]
+    for k, a, b in zip(names, got, ref):
+        tol = 2e-2 if k in ("out", "g_x0") else 2e-3
+        err = rel_err(to_np64(a), to_np64(b))
+        assert err <= tol, (k, err)
